@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the Streaming DiLoCo fragment outer step on one MI355X.
+
+A "step" is one outer step of one fragment: for every run of the fragment, the outer
+gradient of each of the M bf16 replicas, its E3M0 (or other) encoding, decode + fp32
+mean, Nesterov update of the fp32 global parameters and momentum, and the alpha-merge
+into the M locally advanced replicas -- one call of sdl_fragment_outer_step_plan, which
+is a single kernel launch for the decoder shapes used here.  Inputs are resident in HBM
+before the timed region starts.
+
+Prints ONE JSON line.  `value` is parameters of the fragment per second; `roofline`
+prices the fused kernel against the 8 TB/s HBM peak using the algorithmic bytes
+(16 + 6*M bytes per parameter with an overlap delay, 16 + 4*M without); `cpu_baseline`
+is the CPU oracle timed on a bounded sample of the same workload on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+DEFAULT_FRAGMENT = {"tiny": 0, "100m": 1, "1b": 1, "4b_p6": 1, "4b_p1": 0, "stress": 1}
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by
+# the reading of the copy kernel); see profiles/.  None = not measured for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_bytes_per_param(M: int, tau: int) -> float:
+    # read g, mom (8) + w_send (2M) [+ w_now (2M) if it is a different array]; write g, mom (8) + w_now (2M)
+    return 16.0 + (6.0 if tau > 0 else 4.0) * M
+
+
+class State:
+    """Flat model arrays in HBM and the plan of one workload."""
+
+    def __init__(self, wl, sdl, workloads, torch, fragment: int, M: int):
+        self.wl, self.M = wl, M
+        dev = "cuda"
+        if wl.shape is None:
+            numel, block, L = [wl.flat_numel], [0], 1
+        else:
+            shape = workloads.SHAPES[wl.shape]
+            numel, block, _ = shape.units()
+            L = shape.n_layers
+        self.plan = sdl.sdl_fragment_plan(numel, block, L, wl.P, sdl.PATTERN_STRIDED, wl.H, wl.tau)
+        total = self.plan.total_numel
+        self.g = torch.empty(total, dtype=torch.float32, device=dev)
+        self.mom = torch.empty(total, dtype=torch.float32, device=dev)
+        self.w_send = [torch.empty(total, dtype=torch.bfloat16, device=dev) for _ in range(M)]
+        self.w_now = self.w_send if wl.tau == 0 else \
+            [torch.empty(total, dtype=torch.bfloat16, device=dev) for _ in range(M)]
+        self.spans = sdl.sdl_plan_fragment_spans(self.plan, fragment)
+        self.runs = sdl.sdl_plan_fragment_runs(self.plan, fragment)
+        self.n = sum(n for _, n, _ in self.spans)
+        for off, n, unit in self.spans:
+            sl = slice(off, off + n)
+            workloads.fill_span(self.g[sl], self.mom[sl], [w[sl] for w in self.w_send],
+                                [w[sl] for w in self.w_now], unit=unit, tau=wl.tau, delta=wl.delta,
+                                base_seed=wl.seed)
+
+
+def time_gpu(torch, fn, steps: int, warmup: int) -> float:
+    """Average milliseconds per call of fn, HIP events on the current stream around `steps` calls."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(steps):
+        fn()
+    end.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(end) / steps
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="1b", choices=sorted(DEFAULT_FRAGMENT))
+    ap.add_argument("--fragment", type=int, default=None)
+    ap.add_argument("--format", default=None, choices=["e3m0", "e4m3", "bf16", "fp32"])
+    ap.add_argument("--workers", type=int, default=None, help="override M")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the unfused / copy side measurements")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (the M workers are M replicas resident in one "
+              "GPU's HBM; there is no multi-GPU path). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2501_18512_amd as sdl
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU path.", file=sys.stderr)
+        return 2
+    wl = workloads.WORKLOADS[args.workload]
+    M = args.workers or wl.M
+    fmt_name = args.format or wl.fmt
+    fmt = sdl.FORMATS[fmt_name]
+    frag = DEFAULT_FRAGMENT[args.workload] if args.fragment is None else args.fragment
+    st = State(wl, sdl, workloads, torch, frag, M)
+    torch.cuda.synchronize()
+
+    # ---- CPU baseline sample is taken from the untouched inputs (before any GPU step)
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(st, fmt, torch, workloads)
+
+    def step():
+        sdl.sdl_fragment_outer_step_plan(st.plan, frag, st.g, st.mom, st.w_send, st.w_now, fmt, wl.lr, wl.mu,
+                                         wl.alpha)
+
+    n_launch = -(-len(st.runs) // 16)
+    ms = time_gpu(torch, step, args.steps, args.warmup)
+    bpp = algorithmic_bytes_per_param(M, wl.tau)
+    launch_ms = ms / n_launch
+    achieved = bpp * st.n / n_launch / (launch_ms * 1e-3) / 1e9
+    out = {
+        "metric": "fragment_outer_step_params_per_s",
+        "value": st.n / (ms * 1e-3),
+        "unit": "params/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{wl.name}: fragment {frag} of P={wl.P} strided ({wl.shape or 'flat'} decoder shape), "
+                        f"{st.n} params in {len(st.runs)} runs, M={M} bf16 replicas, {fmt_name} exchange, "
+                        f"tau={wl.tau}, alpha={wl.alpha}, lr={wl.lr}, mu={wl.mu}, deltas={wl.delta}",
+            "fragment_params": st.n, "M": M, "format": fmt_name, "tau": wl.tau, "alpha": wl.alpha,
+            "launches_per_step": n_launch,
+        },
+        "roofline": {
+            "bound": "hbm", "kernel": "sdl_kernel<fused>", "achieved": achieved, "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, M, fmt_name)),
+            "algorithmic_bytes_per_param": bpp, "bytes_per_launch": bpp * st.n / n_launch,
+            "launch_ms": launch_ms,
+        },
+        "cpu_baseline": cpu,
+    }
+    if not args.no_extras:
+        out["extras"] = extras(st, fmt, wl, M, torch, sdl, args)
+    print(json.dumps(out))
+    return 0
+
+
+def cpu_baseline(st, fmt, torch, workloads):
+    """The oracle's fused step on the first 2^24 parameters of the fragment (block aligned), with
+    the host threads the box offers to one GPU job (at most 16)."""
+    import oracle
+
+    off, n, _ = st.runs[0]
+    n = min(n, 1 << 24)
+    sl = slice(off, off + n)
+    hg, hmom = st.g[sl].cpu().numpy().copy(), st.mom[sl].cpu().numpy().copy()
+    hs = [workloads.bf16_bits(w[sl]) for w in st.w_send]
+    hn = hs if st.wl.tau == 0 else [workloads.bf16_bits(w[sl]) for w in st.w_now]
+    threads = max(1, min(16, os.cpu_count() or 1))
+    oracle.build()
+    t0 = time.perf_counter()
+    used = oracle.fragment_outer_step_chunked(hg, hmom, hs, hn, fmt, st.wl.lr, st.wl.mu, st.wl.alpha, threads)
+    dt = time.perf_counter() - t0
+    return {"value": n / dt, "unit": "params/s", "cores": min(threads, used), "kind": "oracle",
+            "sample": f"first {n} parameters of the fragment, M={st.M}, same inputs, {dt:.2f} s wall"}
+
+
+def extras(st, fmt, wl, M, torch, sdl, args):
+    """Side measurements on the largest run of the fragment: the three unfused calls and the
+    plain copy kernel (the practical HBM ceiling)."""
+    off, n, _ = max(st.runs, key=lambda r: r[1])
+    sl = slice(off, off + n)
+    g, mom = st.g[sl], st.mom[sl]
+    ws, wn = [w[sl] for w in st.w_send], [w[sl] for w in st.w_now]
+    codes, scales = sdl.alloc_exchange(fmt, n, M)
+    cb, sb = sdl.sdl_exchange_bytes(fmt, n)
+    steps, warm = max(5, args.steps // 2), 3
+    res = {"run_params": n}
+    t = time_gpu(torch, lambda: sdl.sdl_quantize_outer_grad(g, ws, n, fmt, codes, scales), steps, warm)
+    res["quantize"] = {"ms": t, "GB/s": (4 + 2 * M) * n / t / 1e6 + M * (cb + sb) / t / 1e6}
+    t = time_gpu(torch, lambda: sdl.sdl_dequant_reduce_nesterov(g, mom, codes, scales, n, fmt, wl.lr, wl.mu),
+                 steps, warm)
+    res["dequant_reduce_nesterov"] = {"ms": t, "GB/s": (16 * n + M * (cb + sb)) / t / 1e6}
+    t = time_gpu(torch, lambda: sdl.sdl_merge_overlap(g, wn, n, wl.alpha), steps, warm)
+    res["merge_overlap"] = {"ms": t, "GB/s": (4 + 4 * M) * n / t / 1e6}
+    t = time_gpu(torch, lambda: sdl.sdl_fragment_outer_step(g, mom, ws, wn, n, fmt, wl.lr, wl.mu, wl.alpha),
+                 steps, warm)
+    res["fused_single_run"] = {"ms": t, "GB/s": algorithmic_bytes_per_param(M, wl.tau) * n / t / 1e6}
+    nbytes = (4 * n) // 16 * 16
+    src = st.g[sl]
+    dst = torch.empty_like(src)
+    t = time_gpu(torch, lambda: sdl.sdl_copy_bytes(dst, src, nbytes), steps, warm)
+    res["copy_kernel"] = {"ms": t, "GB/s": 2 * nbytes / t / 1e6, "bytes": nbytes}
+    return res
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,198 @@
+/*
+ * sdl.h -- C ABI of the Streaming DiLoCo fragment outer step for AMD MI355X (gfx950).
+ *
+ * One fragment of the model is synchronised per call sequence:
+ *
+ *   send side      sdl_quantize_outer_grad       outer gradient of every replica,
+ *                                                encoded in the exchange format
+ *   receive side   sdl_dequant_reduce_nesterov   decode, fp32 mean over replicas,
+ *                                                Nesterov outer optimizer
+ *                  sdl_merge_overlap             alpha-mix into every replica
+ *   or fused       sdl_fragment_outer_step       all of the above in one pass
+ *
+ * and sdl_fragment_plan builds the fragment map and the send/receive schedule on
+ * the host.  The M replicas ("workers") are M parameter arrays resident in one
+ * GPU's memory; no call communicates with another device.
+ *
+ * Conventions for every call
+ *   - Returns an sdl_status_t (0 = SDL_OK, negative = error).  Never throws, never
+ *     aborts.  On error nothing has been launched and no output was touched.
+ *   - Argument checks run synchronously on the host.  Kernels are enqueued on
+ *     `stream` (a hipStream_t passed as void*, NULL = the default stream) and the
+ *     call returns without waiting for them.
+ *   - "device" pointers are HIP device addresses owned by the caller; the library
+ *     allocates and frees no device memory.  Arrays of pointers (w_send, w_now,
+ *     codes, scales) are HOST arrays of M DEVICE pointers, read during the call.
+ *   - n is the number of parameters of one contiguous span; any n >= 0 is
+ *     accepted (n == 0 is a no-op).  Scale blocks are the 32-element groups
+ *     [32k, 32k+32) counted from the start of the span; the last may be partial.
+ *   - fp32 arrays must be 4-byte aligned, bf16 arrays 2-byte aligned, code and
+ *     scale arrays as the format needs (4 / 2 / 1 / 1 bytes for FP32 / BF16 /
+ *     E4M3 / E3M0).  Arrays aligned to 16 bytes take the fast path; anything else
+ *     is handled by a slower element-wise path with identical results.
+ *     Misaligned pointers give SDL_ERR_ALIGNMENT.
+ *   - 1 <= M <= SDL_MAX_WORKERS.
+ *   - No two arrays may overlap, except that w_send[m] may be the very same
+ *     pointer as w_now[m] for every m (no overlap delay, tau = 0).
+ *   - Non-finite inputs: a block that contains Inf or NaN gets scale byte 0xff and
+ *     decodes to NaN in every element (E3M0 / E4M3); BF16 / FP32 carry them through.
+ */
+#ifndef SDL_H
+#define SDL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SDL_MAX_WORKERS 16
+#define SDL_BLOCK 32           /* elements per scale byte */
+#define SDL_UNIT_PRE  (-1)     /* parameter group before the first block (embedding) */
+#define SDL_UNIT_POST (-2)     /* parameter group after the last block (final norm, head) */
+
+typedef enum {
+    SDL_OK = 0,
+    SDL_ERR_INVALID_ARG = -1,  /* NULL where not allowed, M out of range, bad enum, tau >= H ... */
+    SDL_ERR_UNSUPPORTED = -2,
+    SDL_ERR_ALIGNMENT = -3,    /* pointer not aligned to its element type */
+    SDL_ERR_DEVICE = -4,       /* HIP reported an error at launch */
+    SDL_ERR_NOMEM = -5         /* host allocation failed (plan only) */
+} sdl_status_t;
+
+/* Exchange format of the outer gradients (Section 2.4: lower precision for the
+ * exchanged outer gradients, down to a 4-bit float with 1 sign, 3 exponent and 0
+ * mantissa bits; Section 3.3.3 ablates float32 down to float4).
+ *   SDL_FMT_FP32  no quantisation, 4 bytes / element, no scales
+ *   SDL_FMT_BF16  round-to-nearest-even bfloat16, 2 bytes / element, no scales
+ *   SDL_FMT_E4M3  OCP FP8 E4M3 (bias 7, max 448, saturating), 1 byte / element,
+ *                 plus one power-of-two scale byte per 32 elements
+ *   SDL_FMT_E3M0  code = s<<3 | E, magnitude 0 for E = 0 else 2^(E-3); two codes per
+ *                 byte (element 2j in the low nibble of byte j); plus one scale byte
+ *                 per 32 elements
+ * Scale byte sb means 2^(sb-127); it is chosen from the block's absolute maximum a
+ * as sb = max(0, biased_exponent(a) - emax) with emax = 4 (E3M0) or 8 (E4M3), 0 if
+ * a is zero or subnormal.  Elements are rounded to the nearest representable
+ * magnitude of |x| / 2^(sb-127) in the linear domain, ties to the even code,
+ * saturating at the largest magnitude. */
+typedef enum { SDL_FMT_FP32 = 0, SDL_FMT_BF16 = 1, SDL_FMT_E4M3 = 2, SDL_FMT_E3M0 = 3 } sdl_format_t;
+
+/* Fragment patterns of Section 2.2: interleaved blocks (default) or consecutive blocks. */
+typedef enum { SDL_PATTERN_STRIDED = 0, SDL_PATTERN_SEQUENTIAL = 1 } sdl_pattern_t;
+
+/* A contiguous piece of the flat model that belongs to one fragment.
+ * unit = index of its (first) parameter group in the caller's unit list. */
+typedef struct { uint64_t offset; uint64_t numel; int32_t unit; } sdl_span_t;
+
+typedef struct sdl_plan sdl_plan_t;   /* opaque, host memory, immutable after creation */
+
+/* ------------------------------------------------------------------ plan (host only)
+ *
+ * Section 2.2 and the Require list of Algorithm 2: the model's transformer blocks
+ * are partitioned into P fragments; fragment p has a synchronisation offset t_p; the
+ * overlap delay tau is smaller than H.
+ *
+ * The model is a flat array made of n_units parameter groups in the given order;
+ * unit u has unit_numel[u] elements and belongs to block unit_block[u] in
+ * [0, n_blocks), or to SDL_UNIT_PRE / SDL_UNIT_POST, which travel with the fragment
+ * of block 0 / block n_blocks-1.  Strided: block i -> fragment i mod P.  Sequential:
+ * fragment p owns blocks [floor(p*L/P), floor((p+1)*L/P)).  t_p == NULL selects
+ * t_p = floor(p*H/P); otherwise t_p[p] < H is required.
+ *
+ * Schedule (Algorithm 2's two conditions, with Section 2.2's rule that a fragment
+ * always does H inner steps first): fragment p sends at t = t_p + k*H and receives
+ * at t = t_p + k*H + tau, k = 1, 2, ...
+ *
+ * Errors: SDL_ERR_INVALID_ARG for P == 0, P > n_blocks, H == 0, tau >= H, a block
+ * index out of range, an offset >= H, NULL arrays; SDL_ERR_NOMEM.  *out is set only
+ * on success and must be released with sdl_plan_destroy. */
+int sdl_fragment_plan(const uint64_t* unit_numel, const int32_t* unit_block, uint32_t n_units,
+                      uint32_t n_blocks, uint32_t P, sdl_pattern_t pattern, uint32_t H, uint32_t tau,
+                      const uint32_t* t_p, sdl_plan_t** out);
+void sdl_plan_destroy(sdl_plan_t* plan);
+
+uint32_t sdl_plan_num_fragments(const sdl_plan_t* plan);
+uint64_t sdl_plan_total_numel(const sdl_plan_t* plan);
+/* Fragment that owns transformer block `block`; negative status on bad arguments. */
+int sdl_plan_block_fragment(const sdl_plan_t* plan, uint32_t block);
+/* One span per parameter group of fragment p, in model order.  The array belongs to
+ * the plan. */
+int sdl_plan_fragment_spans(const sdl_plan_t* plan, uint32_t p, const sdl_span_t** spans,
+                            uint32_t* n_spans);
+/* The same elements as maximal contiguous runs: neighbouring spans are joined when
+ * that leaves every 32-element scale block where it was (all joined spans but the
+ * last have a multiple of 32 elements).  Processing the runs instead of the spans
+ * gives identical results with fewer launches. */
+int sdl_plan_fragment_runs(const sdl_plan_t* plan, uint32_t p, const sdl_span_t** runs,
+                           uint32_t* n_runs);
+int sdl_plan_offset(const sdl_plan_t* plan, uint32_t p, uint32_t* t_p);
+/* Fragments that send / receive at inner step t >= 1, ascending p.  send and recv are
+ * caller arrays of capacity P (either may be NULL together with its counter). */
+int sdl_plan_events(const sdl_plan_t* plan, uint64_t t, uint32_t* send, uint32_t* n_send,
+                    uint32_t* recv, uint32_t* n_recv);
+
+/* Bytes of one replica's message for numel elements: returns code_bytes + scale_bytes
+ * and stores the two parts when the pointers are not NULL (0 for an unknown format). */
+size_t sdl_exchange_bytes(sdl_format_t fmt, uint64_t numel, size_t* code_bytes, size_t* scale_bytes);
+
+/* ------------------------------------------------------------------ device calls */
+
+/* Send side (Algorithm 2, "if t - t_p mod H == 0" branch; Section 2.4): for every
+ * replica m, delta_m[i] = g[i] - float(w_send[m][i]) (one fp32 subtraction), encoded
+ * in fmt into codes[m] (and scales[m] for E4M3 / E3M0).
+ *   g        device, fp32[n], read
+ *   w_send   host array of M device pointers to bf16[n], read
+ *   codes    host array of M device pointers, code_bytes each, written
+ *   scales   host array of M device pointers, scale_bytes each, written; may be
+ *            NULL for FP32 / BF16 */
+int sdl_quantize_outer_grad(const float* g, const void* const* w_send, uint32_t M, uint64_t n,
+                            sdl_format_t fmt, void* const* codes, void* const* scales, void* stream);
+
+/* Receive side (Algorithm 2, "if t - t_p - tau mod H == 0" branch; Section 2.4: the
+ * accumulation is done in FP32; Section 2.1: OuterOpt is SGD with Nesterov momentum):
+ *   d[i]   = (sum over m = 0..M-1, in that order, starting from +0, of decode_m[i]) / M
+ *   mom[i] = mu * mom[i] + d[i]
+ *   g[i]   = g[i] - lr * (d[i] + mu * mom[i])          (new mom)
+ * each operation rounded once to fp32.  g and mom (device, fp32[n]) are updated in
+ * place. */
+int sdl_dequant_reduce_nesterov(float* g, float* mom, const void* const* codes,
+                                const void* const* scales, uint32_t M, uint64_t n, sdl_format_t fmt,
+                                float lr, float mu, void* stream);
+
+/* Merge (last statement of Algorithm 2; Section 2.3): for every replica m,
+ *   w_now[m][i] = bf16_rne(alpha * float(w_now[m][i]) + (1 - alpha) * g_new[i])
+ * with 1 - alpha formed once in fp32.  alpha = 1 keeps the replica, alpha = 0
+ * replaces it by the new global parameters.  w_now[m]: device bf16[n], in place. */
+int sdl_merge_overlap(const float* g_new, void* const* w_now, uint32_t M, uint64_t n, float alpha,
+                      void* stream);
+
+/* Fused outer step of one span: the three calls above in a single pass over memory,
+ * with the messages kept in registers.  g, mom and w_now[m] are updated in place;
+ * w_send[m] (the replica as it was at the send step) is only read and may be the same
+ * pointer as w_now[m] for all m.  If codes_or_null is not NULL the messages are also
+ * written out exactly as sdl_quantize_outer_grad would (scales_or_null then must be
+ * given for E4M3 / E3M0). */
+int sdl_fragment_outer_step(float* g, float* mom, const void* const* w_send, void* const* w_now,
+                            uint32_t M, uint64_t n, sdl_format_t fmt, float lr, float mu, float alpha,
+                            void* const* codes_or_null, void* const* scales_or_null, void* stream);
+
+/* Fused outer step of a whole fragment of a plan: every run of fragment p, in one
+ * kernel launch per group of up to 16 runs.  The pointers are the bases of the flat model arrays
+ * (element 0 of the model); run r is processed at element offset runs[r].offset.
+ * Messages are not written. */
+int sdl_fragment_outer_step_plan(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
+                                 const void* const* w_send_base, void* const* w_now_base, uint32_t M,
+                                 sdl_format_t fmt, float lr, float mu, float alpha, void* stream);
+
+/* Plain device-to-device streaming copy of nbytes (a multiple of 16; both pointers
+ * 16-byte aligned).  Not part of the method: it is the yardstick against which the
+ * achieved memory bandwidth of the calls above is judged (2 * nbytes of traffic). */
+int sdl_copy_bytes(void* dst, const void* src, uint64_t nbytes, void* stream);
+
+const char* sdl_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SDL_H */

@@ -1,0 +1,252 @@
+"""Python binding of libsdl.so, the MI355X-native Streaming DiLoCo fragment outer step.
+
+Argument marshalling only: every function has the name and the meaning of the C entry
+point declared in include/sdl.h, takes torch tensors (device memory) where the C call
+takes device pointers, and raises SdlError on a non-zero status.  All arithmetic runs
+in the HIP kernels of the library; there is no Python or CPU fallback, and importing
+this module fails loudly if the library has not been built
+(``python -m paper_2501_18512_amd.build``).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+FMT_FP32, FMT_BF16, FMT_E4M3, FMT_E3M0 = 0, 1, 2, 3
+FORMATS = {"fp32": FMT_FP32, "bf16": FMT_BF16, "e4m3": FMT_E4M3, "e3m0": FMT_E3M0}
+PATTERN_STRIDED, PATTERN_SEQUENTIAL = 0, 1
+UNIT_PRE, UNIT_POST = -1, -2
+MAX_WORKERS = 16
+BLOCK = 32
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsdl.so")
+
+
+class SdlError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {_lib.sdl_status_string(status).decode()} (status {status})")
+
+
+class _Span(ctypes.Structure):
+    _fields_ = [("offset", ctypes.c_uint64), ("numel", ctypes.c_uint64), ("unit", ctypes.c_int32)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2501_18512_amd.build` "
+                          "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, u32, u64, f32 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_float
+    pp = ctypes.POINTER(ctypes.c_void_p)
+    lib.sdl_fragment_plan.argtypes = [ctypes.POINTER(u64), ctypes.POINTER(ctypes.c_int32), u32, u32, u32,
+                                      ctypes.c_int, u32, u32, ctypes.POINTER(u32), ctypes.POINTER(vp)]
+    lib.sdl_plan_destroy.argtypes = [vp]
+    lib.sdl_plan_destroy.restype = None
+    lib.sdl_plan_num_fragments.argtypes = [vp]
+    lib.sdl_plan_num_fragments.restype = u32
+    lib.sdl_plan_total_numel.argtypes = [vp]
+    lib.sdl_plan_total_numel.restype = u64
+    lib.sdl_plan_block_fragment.argtypes = [vp, u32]
+    for name in ("sdl_plan_fragment_spans", "sdl_plan_fragment_runs"):
+        getattr(lib, name).argtypes = [vp, u32, ctypes.POINTER(ctypes.POINTER(_Span)), ctypes.POINTER(u32)]
+    lib.sdl_plan_offset.argtypes = [vp, u32, ctypes.POINTER(u32)]
+    lib.sdl_plan_events.argtypes = [vp, u64, ctypes.POINTER(u32), ctypes.POINTER(u32),
+                                    ctypes.POINTER(u32), ctypes.POINTER(u32)]
+    lib.sdl_exchange_bytes.argtypes = [ctypes.c_int, u64, ctypes.POINTER(ctypes.c_size_t),
+                                       ctypes.POINTER(ctypes.c_size_t)]
+    lib.sdl_exchange_bytes.restype = ctypes.c_size_t
+    lib.sdl_quantize_outer_grad.argtypes = [vp, pp, u32, u64, ctypes.c_int, pp, pp, vp]
+    lib.sdl_dequant_reduce_nesterov.argtypes = [vp, vp, pp, pp, u32, u64, ctypes.c_int, f32, f32, vp]
+    lib.sdl_merge_overlap.argtypes = [vp, pp, u32, u64, f32, vp]
+    lib.sdl_fragment_outer_step.argtypes = [vp, vp, pp, pp, u32, u64, ctypes.c_int, f32, f32, f32,
+                                            pp, pp, vp]
+    lib.sdl_fragment_outer_step_plan.argtypes = [vp, u32, vp, vp, pp, pp, u32, ctypes.c_int, f32, f32,
+                                                 f32, vp]
+    lib.sdl_copy_bytes.argtypes = [vp, vp, u64, vp]
+    lib.sdl_status_string.argtypes = [ctypes.c_int]
+    lib.sdl_status_string.restype = ctypes.c_char_p
+    return lib
+
+
+_lib = _load()
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise SdlError(status, where)
+
+
+def _ptr(t) -> int:
+    """Device address of a tensor (or a raw integer address, passed through)."""
+    if t is None:
+        return 0
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _ptr_array(ts: Optional[Sequence]):
+    if ts is None:
+        return None
+    return (ctypes.c_void_p * len(ts))(*[_ptr(t) for t in ts])
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _require_device(*tensors):
+    for t in tensors:
+        if isinstance(t, torch.Tensor):
+            if not t.is_cuda:
+                raise ValueError("sdl calls take device tensors; there is no CPU path")
+            if not t.is_contiguous():
+                raise ValueError("sdl calls take contiguous tensors")
+
+
+# ------------------------------------------------------------------------------ plan
+
+class Plan:
+    """Owner of an sdl_plan_t handle."""
+
+    def __init__(self, handle: int):
+        self._h = ctypes.c_void_p(handle)
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.sdl_plan_destroy(self._h)
+            self._h = None
+
+    @property
+    def num_fragments(self) -> int:
+        return _lib.sdl_plan_num_fragments(self._h)
+
+    @property
+    def total_numel(self) -> int:
+        return _lib.sdl_plan_total_numel(self._h)
+
+
+def sdl_fragment_plan(unit_numel: Sequence[int], unit_block: Sequence[int], n_blocks: int, P: int,
+                      pattern: int = PATTERN_STRIDED, H: int = 100, tau: int = 0,
+                      t_p: Optional[Sequence[int]] = None) -> Plan:
+    n = len(unit_numel)
+    assert len(unit_block) == n
+    numel = (ctypes.c_uint64 * n)(*unit_numel)
+    block = (ctypes.c_int32 * n)(*unit_block)
+    offs = None if t_p is None else (ctypes.c_uint32 * len(t_p))(*t_p)
+    if t_p is not None and len(t_p) != P:
+        raise SdlError(-1, "sdl_fragment_plan")
+    out = ctypes.c_void_p()
+    _check(_lib.sdl_fragment_plan(numel, block, n, n_blocks, P, pattern, H, tau, offs,
+                                  ctypes.byref(out)), "sdl_fragment_plan")
+    return Plan(out.value)
+
+
+def _span_list(fn, plan: Plan, p: int) -> List[Tuple[int, int, int]]:
+    arr = ctypes.POINTER(_Span)()
+    n = ctypes.c_uint32()
+    _check(fn(plan._h, p, ctypes.byref(arr), ctypes.byref(n)), fn.__name__)
+    return [(arr[i].offset, arr[i].numel, arr[i].unit) for i in range(n.value)]
+
+
+def sdl_plan_fragment_spans(plan: Plan, p: int):
+    return _span_list(_lib.sdl_plan_fragment_spans, plan, p)
+
+
+def sdl_plan_fragment_runs(plan: Plan, p: int):
+    return _span_list(_lib.sdl_plan_fragment_runs, plan, p)
+
+
+def sdl_plan_block_fragment(plan: Plan, block: int) -> int:
+    rc = _lib.sdl_plan_block_fragment(plan._h, block)
+    if rc < 0:
+        raise SdlError(rc, "sdl_plan_block_fragment")
+    return rc
+
+
+def sdl_plan_offset(plan: Plan, p: int) -> int:
+    out = ctypes.c_uint32()
+    _check(_lib.sdl_plan_offset(plan._h, p, ctypes.byref(out)), "sdl_plan_offset")
+    return out.value
+
+
+def sdl_plan_events(plan: Plan, t: int) -> Tuple[List[int], List[int]]:
+    P = plan.num_fragments
+    send, recv = (ctypes.c_uint32 * P)(), (ctypes.c_uint32 * P)()
+    ns, nr = ctypes.c_uint32(), ctypes.c_uint32()
+    _check(_lib.sdl_plan_events(plan._h, t, send, ctypes.byref(ns), recv, ctypes.byref(nr)),
+           "sdl_plan_events")
+    return list(send[:ns.value]), list(recv[:nr.value])
+
+
+def sdl_exchange_bytes(fmt: int, numel: int) -> Tuple[int, int]:
+    c, s = ctypes.c_size_t(), ctypes.c_size_t()
+    _lib.sdl_exchange_bytes(fmt, numel, ctypes.byref(c), ctypes.byref(s))
+    return c.value, s.value
+
+
+# ------------------------------------------------------------------------ device calls
+
+def sdl_quantize_outer_grad(g, w_send, n: int, fmt: int, codes, scales=None, stream=None):
+    _require_device(g, *w_send, *codes, *(scales or []))
+    _check(_lib.sdl_quantize_outer_grad(_ptr(g), _ptr_array(w_send), len(w_send), n, fmt,
+                                        _ptr_array(codes), _ptr_array(scales), _stream(stream)),
+           "sdl_quantize_outer_grad")
+
+
+def sdl_dequant_reduce_nesterov(g, mom, codes, scales, n: int, fmt: int, lr: float, mu: float,
+                                stream=None):
+    _require_device(g, mom, *codes, *(scales or []))
+    _check(_lib.sdl_dequant_reduce_nesterov(_ptr(g), _ptr(mom), _ptr_array(codes), _ptr_array(scales),
+                                            len(codes), n, fmt, lr, mu, _stream(stream)),
+           "sdl_dequant_reduce_nesterov")
+
+
+def sdl_merge_overlap(g_new, w_now, n: int, alpha: float, stream=None):
+    _require_device(g_new, *w_now)
+    _check(_lib.sdl_merge_overlap(_ptr(g_new), _ptr_array(w_now), len(w_now), n, alpha,
+                                  _stream(stream)), "sdl_merge_overlap")
+
+
+def sdl_fragment_outer_step(g, mom, w_send, w_now, n: int, fmt: int, lr: float, mu: float,
+                            alpha: float, codes=None, scales=None, stream=None):
+    _require_device(g, mom, *w_send, *w_now, *(codes or []), *(scales or []))
+    if len(w_send) != len(w_now):
+        raise SdlError(-1, "sdl_fragment_outer_step")
+    _check(_lib.sdl_fragment_outer_step(_ptr(g), _ptr(mom), _ptr_array(w_send), _ptr_array(w_now),
+                                        len(w_send), n, fmt, lr, mu, alpha, _ptr_array(codes),
+                                        _ptr_array(scales), _stream(stream)),
+           "sdl_fragment_outer_step")
+
+
+def sdl_fragment_outer_step_plan(plan: Plan, p: int, g_base, mom_base, w_send_base, w_now_base,
+                                 fmt: int, lr: float, mu: float, alpha: float, stream=None):
+    _require_device(g_base, mom_base, *w_send_base, *w_now_base)
+    if len(w_send_base) != len(w_now_base):
+        raise SdlError(-1, "sdl_fragment_outer_step_plan")
+    _check(_lib.sdl_fragment_outer_step_plan(plan._h, p, _ptr(g_base), _ptr(mom_base),
+                                             _ptr_array(w_send_base), _ptr_array(w_now_base),
+                                             len(w_send_base), fmt, lr, mu, alpha, _stream(stream)),
+           "sdl_fragment_outer_step_plan")
+
+
+def sdl_copy_bytes(dst, src, nbytes: int, stream=None):
+    _require_device(dst, src)
+    _check(_lib.sdl_copy_bytes(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "sdl_copy_bytes")
+
+
+def alloc_exchange(fmt: int, n: int, M: int, device="cuda"):
+    """Device buffers for M messages of n elements: (codes, scales) lists of uint8 tensors."""
+    cb, sb = sdl_exchange_bytes(fmt, n)
+    codes = [torch.empty(max(cb, 16), dtype=torch.uint8, device=device) for _ in range(M)]
+    scales = [torch.empty(max(sb, 16), dtype=torch.uint8, device=device) for _ in range(M)]
+    return codes, scales
