@@ -1,12 +1,20 @@
 // Device side of the library: the streaming kernels of the fragment outer step for
 // gfx950 (MI355X), and the C entry points that launch them.
 //
-// Work decomposition (all four kernels): one lane owns 8 consecutive parameters, so a
-// quad of lanes owns one 32-element scale block and a 256-lane workgroup owns 2048
-// parameters.  Per replica a lane moves one 128-bit word of bf16, per fp32 array two.
-// The block maximum is a 2-step DPP exchange inside the quad; nothing goes through
-// LDS.  A launch covers up to kMaxRuns contiguous runs of the flat model; every
-// workgroup belongs to exactly one run, so scale blocks never straddle runs.
+// Work decomposition (all four kernels).  A workgroup is one 64-lane wavefront and owns a
+// tile of 512 consecutive parameters, seen as two rows of 256.  Lane l owns the four
+// parameters [4l, 4l+4) of each row, so
+//   - every memory instruction of the wavefront touches one contiguous piece of an
+//     array (1 KiB of fp32 through 128-bit accesses, 512 B of bf16 through 64-bit
+//     accesses): whole cache lines, nothing strided;
+//   - eight neighbouring lanes own one 32-element scale block, and the block maximum
+//     is three DPP exchanges (two inside the quad, one across the half row); nothing
+//     goes through LDS.
+// Full, 16-byte aligned tiles use buffer instructions with non-temporal cache policy
+// (every byte is touched once); ragged tails and unaligned runs use guarded
+// element-wise accesses.  A launch covers up to kMaxRuns contiguous runs of the flat
+// model; every workgroup belongs to exactly one run, so scale blocks never straddle
+// runs.
 //
 // Arithmetic contract (Algorithm 2 and Sections 2.1, 2.3, 2.4 of the paper, with the
 // exchange formats documented in sdl.h): every fp32 operation is a single IEEE
@@ -21,9 +29,12 @@
 
 namespace {
 
-constexpr int kLane = 8;                      // parameters per lane
-constexpr int kThreads = 256;                 // lanes per workgroup
-constexpr int kGroup = kLane * kThreads;      // parameters per workgroup
+constexpr int kVec = 4;                       // consecutive parameters a lane owns in one row
+constexpr int kRows = 2;                      // rows of a tile
+constexpr int kWave = 64;                     // lanes per workgroup: one wavefront
+constexpr int kRow = kVec * kWave;            // parameters per row (256)
+constexpr int kGroup = kRow * kRows;          // parameters per workgroup tile (512)
+constexpr int kBlockLanes = SDL_BLOCK / kVec; // lanes that share a scale block (8)
 constexpr int kMaxRuns = 16;                  // runs per launch
 
 enum Mode { kQuantize = 0, kReduce = 1, kMerge = 2, kFused = 3 };
@@ -50,6 +61,29 @@ struct Args {
     uint32_t emit;       // fused kernel: also write the messages
 };
 
+// Cache policy bits of the buffer instructions on gfx950: 1 = sc0, 2 = nt, 16 = sc1.
+#ifndef SDL_AUX_LD
+#define SDL_AUX_LD 2         // loads: non-temporal
+#endif
+#ifndef SDL_AUX_ST
+#define SDL_AUX_ST 2         // stores: non-temporal
+#endif
+
+#ifndef SDL_SERIALIZE_FROM
+#define SDL_SERIALIZE_FROM 4
+#endif
+#ifndef SDL_WAVES_PER_EU
+#define SDL_WAVES_PER_EU 2   // register budget: at least this many wavefronts per SIMD
+#endif
+#ifndef SDL_LDS_BYTES
+#define SDL_LDS_BYTES 0      // dynamic LDS requested per workgroup, only to cap the wavefronts per CU
+#endif
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
 // ------------------------------------------------------------------ bit helpers
 
 __device__ __forceinline__ uint32_t f2u(float x) { return __builtin_bit_cast(uint32_t, x); }
@@ -59,94 +93,34 @@ __device__ __forceinline__ float u2f(uint32_t u) { return __builtin_bit_cast(flo
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return u2f(u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return u2f(u & 0xffff0000u); }
 
-// fp32 -> bf16 bits, round to nearest even, NaN kept quiet.
-__device__ __forceinline__ uint32_t bf16_rne(float x)
-{
-    uint32_t u = f2u(x);
-    uint32_t r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-    return ((u & 0x7fffffffu) > 0x7f800000u) ? ((u >> 16) | 0x40u) : r;
-}
+// Two fp32 -> packed bf16, round to nearest even, NaN stays a quiet NaN (v_cvt_pk_bf16_f32).
 __device__ __forceinline__ uint32_t bf16_pack(float lo, float hi)
 {
-    return bf16_rne(lo) | (bf16_rne(hi) << 16);
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
-// Maximum over the four lanes of a quad (two DPP quad-permute exchanges).
-__device__ __forceinline__ uint32_t quad_max(uint32_t v)
+__device__ __forceinline__ void unpack_bf16(const uint32_t (&u)[2], float (&v)[kVec])
 {
-    uint32_t t = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);   // lanes 1,0,3,2
+    v[0] = bf16_lo(u[0]); v[1] = bf16_hi(u[0]); v[2] = bf16_lo(u[1]); v[3] = bf16_hi(u[1]);
+}
+
+// Maximum over the eight lanes that share a scale block: lanes 8k .. 8k+7.
+__device__ __forceinline__ uint32_t block_max(uint32_t v)
+{
+    uint32_t t = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);    // quad_perm 1,0,3,2
     v = v > t ? v : t;
-    t = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xF, 0xF, true);            // lanes 2,3,0,1
+    t = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xF, 0xF, true);             // quad_perm 2,3,0,1
+    v = v > t ? v : t;
+    t = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x141, 0xF, 0xF, true);            // row_half_mirror: 7-i
     return v > t ? v : t;
-}
-
-// ------------------------------------------------------------------ tile loads / stores
-// fast: the lane's 8 elements are all valid and the arrays are 16-byte aligned.
-
-__device__ __forceinline__ void load_f32(const float* p, int valid, bool fast, float (&v)[kLane])
-{
-    if (fast) {
-        const float4 a = reinterpret_cast<const float4*>(p)[0];
-        const float4 b = reinterpret_cast<const float4*>(p)[1];
-        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
-        v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-    } else {
-#pragma unroll
-        for (int j = 0; j < kLane; ++j) v[j] = j < valid ? p[j] : 0.0f;
-    }
-}
-
-__device__ __forceinline__ void store_f32(float* p, int valid, bool fast, const float (&v)[kLane])
-{
-    if (fast) {
-        reinterpret_cast<float4*>(p)[0] = make_float4(v[0], v[1], v[2], v[3]);
-        reinterpret_cast<float4*>(p)[1] = make_float4(v[4], v[5], v[6], v[7]);
-    } else {
-#pragma unroll
-        for (int j = 0; j < kLane; ++j)
-            if (j < valid) p[j] = v[j];
-    }
-}
-
-__device__ __forceinline__ void load_bf16(const uint16_t* p, int valid, bool fast, uint32_t (&u)[4])
-{
-    if (fast) {
-        const uint4 a = reinterpret_cast<const uint4*>(p)[0];
-        u[0] = a.x; u[1] = a.y; u[2] = a.z; u[3] = a.w;
-    } else {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            uint32_t lo = 2 * k < valid ? p[2 * k] : 0u;
-            uint32_t hi = 2 * k + 1 < valid ? p[2 * k + 1] : 0u;
-            u[k] = lo | (hi << 16);
-        }
-    }
-}
-
-__device__ __forceinline__ void store_bf16(uint16_t* p, int valid, bool fast, const uint32_t (&u)[4])
-{
-    if (fast) {
-        reinterpret_cast<uint4*>(p)[0] = make_uint4(u[0], u[1], u[2], u[3]);
-    } else {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            if (2 * k < valid) p[2 * k] = (uint16_t)(u[k] & 0xffffu);
-            if (2 * k + 1 < valid) p[2 * k + 1] = (uint16_t)(u[k] >> 16);
-        }
-    }
-}
-
-__device__ __forceinline__ void unpack_bf16(const uint32_t (&u)[4], float (&v)[kLane])
-{
-#pragma unroll
-    for (int k = 0; k < 4; ++k) { v[2 * k] = bf16_lo(u[k]); v[2 * k + 1] = bf16_hi(u[k]); }
 }
 
 // ------------------------------------------------------------------ exchange formats
 // A message element is produced in two forms: its decoded fp32 value dq (what the
 // receiver accumulates) and, when asked for, its code.
 
-template <int FMT> struct BlockScale {       // per quad (32-element block) quantities
+struct BlockScale {
     uint32_t sb;      // scale byte
     float inv;        // 2^(127-sb), or 0 for a degenerate block
     float scale;      // 2^(sb-127), NaN for a block that holds Inf/NaN
@@ -154,10 +128,10 @@ template <int FMT> struct BlockScale {       // per quad (32-element block) quan
 };
 
 template <int FMT>
-__device__ __forceinline__ BlockScale<FMT> block_scale_from_exponent(uint32_t e_a)
+__device__ __forceinline__ BlockScale block_scale_from_exponent(uint32_t e_a)
 {
     constexpr uint32_t emax = (FMT == SDL_FMT_E3M0) ? 4u : 8u;
-    BlockScale<FMT> b;
+    BlockScale b;
     b.sb = e_a > emax ? e_a - emax : 0u;
     b.degenerate = (e_a == 0u) || (e_a == 255u);
     b.inv = b.degenerate ? 0.0f : u2f((254u - b.sb) << 23);
@@ -172,20 +146,20 @@ __device__ __forceinline__ float scale_from_byte(uint32_t sb)
     return sb == 255u ? u2f(0x7fc00000u) : s;
 }
 
-// Encode the lane's 8 outer gradients d of one replica.  dq = decoded values.  codes:
-// E3M0 -> c[0] holds 8 nibbles; E4M3 -> c[0..1] hold 8 bytes; BF16 -> c[0..3];
-// FP32 -> the bits of d.  sb = scale byte of the lane's block (scaled formats).
+// Encode the lane's 4 outer gradients d of one row and one replica.  dq = decoded
+// values.  Codes: E3M0 -> c[0] holds 4 nibbles (16 bits); E4M3 -> c[0] holds 4 bytes;
+// BF16 -> c[0..1]; FP32 -> the bits of d.  sb = scale byte of the lane's block.
 template <int FMT>
-__device__ __forceinline__ void encode(const float (&d)[kLane], float (&dq)[kLane], uint32_t (&c)[kLane],
+__device__ __forceinline__ void encode(const float (&d)[kVec], float (&dq)[kVec], uint32_t (&c)[kVec],
                                        uint32_t& sb, bool want_codes)
 {
     if constexpr (FMT == SDL_FMT_FP32) {
 #pragma unroll
-        for (int j = 0; j < kLane; ++j) { dq[j] = d[j]; c[j] = f2u(d[j]); }
+        for (int j = 0; j < kVec; ++j) { dq[j] = d[j]; c[j] = f2u(d[j]); }
         sb = 0;
     } else if constexpr (FMT == SDL_FMT_BF16) {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
+        for (int k = 0; k < 2; ++k) {
             c[k] = bf16_pack(d[2 * k], d[2 * k + 1]);
             dq[2 * k] = bf16_lo(c[k]);
             dq[2 * k + 1] = bf16_hi(c[k]);
@@ -194,16 +168,16 @@ __device__ __forceinline__ void encode(const float (&d)[kLane], float (&dq)[kLan
     } else {
         uint32_t amax = 0;
 #pragma unroll
-        for (int j = 0; j < kLane; ++j) {
-            uint32_t m = f2u(d[j]) & 0x7fffffffu;
+        for (int j = 0; j < kVec; ++j) {
+            const uint32_t m = f2u(d[j]) & 0x7fffffffu;
             amax = m > amax ? m : amax;
         }
-        amax = quad_max(amax);
-        const BlockScale<FMT> b = block_scale_from_exponent<FMT>(amax >> 23);
+        amax = block_max(amax);
+        const BlockScale b = block_scale_from_exponent<FMT>(amax >> 23);
         sb = b.sb;
-        uint32_t packed0 = 0, packed1 = 0;
+        uint32_t packed = 0;
 #pragma unroll
-        for (int j = 0; j < kLane; ++j) {
+        for (int j = 0; j < kVec; ++j) {
             const float y = __builtin_fabsf(d[j]) * b.inv;     // exact power-of-two scaling
             const uint32_t yb = f2u(y);
             const uint32_t sign = f2u(d[j]) & 0x80000000u;
@@ -227,112 +201,384 @@ __device__ __forceinline__ void encode(const float (&d)[kLane], float (&dq)[kLan
             if (want_codes) {
                 if constexpr (FMT == SDL_FMT_E3M0) {
                     const uint32_t E = val == 0.0f ? 0u : (f2u(val) >> 23) - 124u;
-                    packed0 |= ((sign >> 28) | E) << (4 * j);
+                    packed |= ((sign >> 28) | E) << (4 * j);
                 } else {
                     const uint32_t mag = val < 0.015625f ? (uint32_t)(val * 512.0f)
                                                          : (f2u(val) >> 20) - 960u;
-                    const uint32_t byte = (sign >> 24) | mag;
-                    if (j < 4) packed0 |= byte << (8 * j); else packed1 |= byte << (8 * (j - 4));
+                    packed |= ((sign >> 24) | mag) << (8 * j);
                 }
             }
         }
-        c[0] = packed0; c[1] = packed1;
+        c[0] = packed;
     }
 }
 
-// Decode the lane's 8 message elements of one replica from memory.
-template <int FMT>
-__device__ __forceinline__ void load_decode(const uint8_t* codes, const uint8_t* scales, uint64_t base,
-                                            int valid, bool fast, float (&dq)[kLane])
+// Decode 4 E3M0 nibbles / 4 E4M3 bytes under the block scale.
+__device__ __forceinline__ void decode_e3m0(uint32_t c0, float scale, float (&dq)[kVec])
 {
-    if constexpr (FMT == SDL_FMT_FP32) {
-        load_f32(reinterpret_cast<const float*>(codes) + base, valid, fast, dq);
-    } else if constexpr (FMT == SDL_FMT_BF16) {
-        uint32_t u[4];
-        load_bf16(reinterpret_cast<const uint16_t*>(codes) + base, valid, fast, u);
-        unpack_bf16(u, dq);
-    } else {
-        const uint32_t sb = valid > 0 ? scales[base / SDL_BLOCK] : 127u;
-        const float scale = scale_from_byte(sb);
-        uint32_t c0 = 0, c1 = 0;
-        if constexpr (FMT == SDL_FMT_E3M0) {
-            if (fast) {
-                c0 = *reinterpret_cast<const uint32_t*>(codes + base / 2);
-            } else {
 #pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    if (2 * k < valid) c0 |= (uint32_t)codes[base / 2 + k] << (8 * k);
-            }
+    for (int j = 0; j < kVec; ++j) {
+        const uint32_t nib = (c0 >> (4 * j)) & 15u;
+        const uint32_t E = nib & 7u;
+        const float val = E ? u2f((E + 124u) << 23) : 0.0f;
+        dq[j] = u2f(((nib & 8u) << 28) | f2u(val * scale));
+    }
+}
+__device__ __forceinline__ void decode_e4m3(uint32_t c0, float scale, float (&dq)[kVec])
+{
 #pragma unroll
-            for (int j = 0; j < kLane; ++j) {
-                const uint32_t nib = (c0 >> (4 * j)) & 15u;
-                const uint32_t E = nib & 7u;
-                const float val = E ? u2f((E + 124u) << 23) : 0.0f;
-                dq[j] = u2f(((nib & 8u) << 28) | f2u(val * scale));
-            }
+    for (int j = 0; j < kVec; ++j) {
+        const uint32_t byte = (c0 >> (8 * j)) & 255u;
+        const uint32_t mag = byte & 0x7fu;
+        const float val = mag >= 8u ? u2f((mag + 960u) << 20) : (float)mag * 0.001953125f;
+        dq[j] = u2f(((byte & 0x80u) << 24) | f2u(val * scale));
+    }
+}
+
+// ------------------------------------------------------------------ tile I/O policies
+// The arithmetic is written once against an I/O policy that moves a lane's 4 elements
+// of row `row` of each array.
+//   TileIO     a whole, 16-byte aligned tile: buffer loads / stores through one resource
+//              per array (scalar base, 32-bit lane offset) with explicit cache policy
+//   GuardedIO  any alignment, any tail: per-element global loads / stores under a
+//              per-row count of valid elements
+
+struct TileIO {
+    const Args& a;
+    uint64_t t0;      // tile's first element in the flat arrays (workgroup uniform)
+    uint64_t tb;      // tile's first element counted from the run start (a multiple of 512)
+    uint32_t lane;
+
+    static __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* p, uint32_t bytes)
+    {
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+    }
+    // p = address of the tile's first element in the array
+    __device__ __forceinline__ void ld_f32(const float* p, int row, float (&v)[kVec]) const
+    {
+        const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rsrc(p, kGroup * 4),
+                                                              (int)(row * kRow * 4 + lane * 16), 0, SDL_AUX_LD);
+        v[0] = u2f(x.x); v[1] = u2f(x.y); v[2] = u2f(x.z); v[3] = u2f(x.w);
+    }
+    __device__ __forceinline__ void st_f32(float* p, int row, const float (&v)[kVec]) const
+    {
+        const u32x4 x = {f2u(v[0]), f2u(v[1]), f2u(v[2]), f2u(v[3])};
+        __builtin_amdgcn_raw_buffer_store_b128(x, rsrc(p, kGroup * 4), (int)(row * kRow * 4 + lane * 16), 0,
+                                               SDL_AUX_ST);
+    }
+    __device__ __forceinline__ void ld_bf16(const uint16_t* p, int row, uint32_t (&u)[2]) const
+    {
+        const u32x2 x = __builtin_amdgcn_raw_buffer_load_b64(rsrc(p, kGroup * 2),
+                                                             (int)(row * kRow * 2 + lane * 8), 0, SDL_AUX_LD);
+        u[0] = x.x; u[1] = x.y;
+    }
+    __device__ __forceinline__ void st_bf16(uint16_t* p, int row, const uint32_t (&u)[2]) const
+    {
+        const u32x2 x = {u[0], u[1]};
+        __builtin_amdgcn_raw_buffer_store_b64(x, rsrc(p, kGroup * 2), (int)(row * kRow * 2 + lane * 8), 0,
+                                              SDL_AUX_ST);
+    }
+
+    __device__ __forceinline__ void load_g(int row, float (&v)[kVec]) const { ld_f32(a.g + t0, row, v); }
+    __device__ __forceinline__ void load_mom(int row, float (&v)[kVec]) const { ld_f32(a.mom + t0, row, v); }
+    __device__ __forceinline__ void store_g(int row, const float (&v)[kVec]) const { st_f32(a.g + t0, row, v); }
+    __device__ __forceinline__ void store_mom(int row, const float (&v)[kVec]) const { st_f32(a.mom + t0, row, v); }
+    __device__ __forceinline__ void load_ws(uint32_t m, int row, uint32_t (&u)[2]) const { ld_bf16(a.w_send[m] + t0, row, u); }
+    __device__ __forceinline__ void load_wn(uint32_t m, int row, uint32_t (&u)[2]) const { ld_bf16(a.w_now[m] + t0, row, u); }
+    __device__ __forceinline__ void store_wn(uint32_t m, int row, const uint32_t (&u)[2]) const { st_bf16(a.w_now[m] + t0, row, u); }
+
+    template <int FMT> __device__ __forceinline__ void load_message(uint32_t m, int row, float (&dq)[kVec]) const
+    {
+        const uint8_t* codes = a.codes[m];
+        if constexpr (FMT == SDL_FMT_FP32) {
+            ld_f32(reinterpret_cast<const float*>(codes) + tb, row, dq);
+        } else if constexpr (FMT == SDL_FMT_BF16) {
+            uint32_t u[2];
+            ld_bf16(reinterpret_cast<const uint16_t*>(codes) + tb, row, u);
+            unpack_bf16(u, dq);
         } else {
-            if (fast) {
-                const uint2 w = *reinterpret_cast<const uint2*>(codes + base);
-                c0 = w.x; c1 = w.y;
+            const uint32_t sb = __builtin_amdgcn_raw_buffer_load_b8(
+                rsrc(a.scales[m] + tb / SDL_BLOCK, kGroup / SDL_BLOCK),
+                (int)(row * (kRow / SDL_BLOCK) + lane / kBlockLanes), 0, SDL_AUX_LD);
+            const float scale = scale_from_byte(sb);
+            if constexpr (FMT == SDL_FMT_E3M0) {
+                const uint32_t c0 = __builtin_amdgcn_raw_buffer_load_b16(rsrc(codes + tb / 2, kGroup / 2),
+                                                                         (int)(row * (kRow / 2) + lane * 2), 0,
+                                                                         SDL_AUX_LD);
+                decode_e3m0(c0, scale, dq);
             } else {
-#pragma unroll
-                for (int j = 0; j < kLane; ++j) {
-                    uint32_t byte = j < valid ? codes[base + j] : 0u;
-                    if (j < 4) c0 |= byte << (8 * j); else c1 |= byte << (8 * (j - 4));
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < kLane; ++j) {
-                const uint32_t byte = ((j < 4 ? c0 : c1) >> (8 * (j & 3))) & 255u;
-                const uint32_t mag = byte & 0x7fu;
-                const float val = mag >= 8u ? u2f((mag + 960u) << 20) : (float)mag * 0.001953125f;
-                dq[j] = u2f(((byte & 0x80u) << 24) | f2u(val * scale));
+                const uint32_t c0 = __builtin_amdgcn_raw_buffer_load_b32(rsrc(codes + tb, kGroup),
+                                                                         (int)(row * kRow + lane * 4), 0, SDL_AUX_LD);
+                decode_e4m3(c0, scale, dq);
             }
         }
     }
-}
-
-// Write the lane's part of one replica's message.
-template <int FMT>
-__device__ __forceinline__ void store_codes(uint8_t* codes, uint8_t* scales, uint64_t base, int valid,
-                                            bool fast, const uint32_t (&c)[kLane], uint32_t sb)
-{
-    if constexpr (FMT == SDL_FMT_FP32) {
-        float v[kLane];
-#pragma unroll
-        for (int j = 0; j < kLane; ++j) v[j] = u2f(c[j]);
-        store_f32(reinterpret_cast<float*>(codes) + base, valid, fast, v);
-    } else if constexpr (FMT == SDL_FMT_BF16) {
-        const uint32_t u[4] = {c[0], c[1], c[2], c[3]};
-        store_bf16(reinterpret_cast<uint16_t*>(codes) + base, valid, fast, u);
-    } else {
-        if ((threadIdx.x & 3u) == 0u && valid > 0) scales[base / SDL_BLOCK] = (uint8_t)sb;
-        if constexpr (FMT == SDL_FMT_E3M0) {
-            if (fast) {
-                *reinterpret_cast<uint32_t*>(codes + base / 2) = c[0];
-            } else {
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    if (2 * k < valid) codes[base / 2 + k] = (uint8_t)(c[0] >> (8 * k));
-            }
+    template <int FMT>
+    __device__ __forceinline__ void store_message(uint32_t m, int row, const uint32_t (&c)[kVec], uint32_t sb) const
+    {
+        uint8_t* codes = a.codes[m];
+        if constexpr (FMT == SDL_FMT_FP32) {
+            const u32x4 x = {c[0], c[1], c[2], c[3]};
+            __builtin_amdgcn_raw_buffer_store_b128(x, rsrc(codes + tb * 4, kGroup * 4),
+                                                   (int)(row * kRow * 4 + lane * 16), 0, SDL_AUX_ST);
+        } else if constexpr (FMT == SDL_FMT_BF16) {
+            const u32x2 x = {c[0], c[1]};
+            __builtin_amdgcn_raw_buffer_store_b64(x, rsrc(codes + tb * 2, kGroup * 2),
+                                                  (int)(row * kRow * 2 + lane * 8), 0, SDL_AUX_ST);
         } else {
-            if (fast) {
-                *reinterpret_cast<uint2*>(codes + base) = make_uint2(c[0], c[1]);
+            if ((lane % kBlockLanes) == 0u)
+                __builtin_amdgcn_raw_buffer_store_b8((uint8_t)sb, rsrc(a.scales[m] + tb / SDL_BLOCK, kGroup / SDL_BLOCK),
+                                                     (int)(row * (kRow / SDL_BLOCK) + lane / kBlockLanes), 0, SDL_AUX_ST);
+            if constexpr (FMT == SDL_FMT_E3M0) {
+                __builtin_amdgcn_raw_buffer_store_b16((uint16_t)c[0], rsrc(codes + tb / 2, kGroup / 2),
+                                                      (int)(row * (kRow / 2) + lane * 2), 0, SDL_AUX_ST);
+            } else {
+                __builtin_amdgcn_raw_buffer_store_b32(c[0], rsrc(codes + tb, kGroup), (int)(row * kRow + lane * 4), 0,
+                                                      SDL_AUX_ST);
+            }
+        }
+    }
+};
+
+struct GuardedIO {
+    const Args& a;
+    uint64_t t0;           // tile's first element in the flat arrays
+    uint64_t tb;           // tile's first element counted from the run start
+    uint64_t run_n;        // elements of the run
+    uint32_t lane;
+
+    // lane's first element of a row, counted from the run start, and how many of its 4 exist
+    __device__ __forceinline__ uint64_t first(int row) const { return tb + (uint64_t)(row * kRow) + lane * kVec; }
+    __device__ __forceinline__ int valid(int row) const
+    {
+        const uint64_t b = first(row);
+        return b >= run_n ? 0 : (run_n - b >= (uint64_t)kVec ? kVec : (int)(run_n - b));
+    }
+    __device__ __forceinline__ uint64_t flat(int row) const { return t0 + (uint64_t)(row * kRow) + lane * kVec; }
+
+    __device__ __forceinline__ void ld_f32(const float* p, int n, float (&v)[kVec]) const
+    {
+#pragma unroll
+        for (int j = 0; j < kVec; ++j) v[j] = j < n ? p[j] : 0.0f;
+    }
+    __device__ __forceinline__ void st_f32(float* p, int n, const float (&v)[kVec]) const
+    {
+#pragma unroll
+        for (int j = 0; j < kVec; ++j)
+            if (j < n) p[j] = v[j];
+    }
+    __device__ __forceinline__ void ld_bf16(const uint16_t* p, int n, uint32_t (&u)[2]) const
+    {
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const uint32_t lo = 2 * k < n ? p[2 * k] : 0u;
+            const uint32_t hi = 2 * k + 1 < n ? p[2 * k + 1] : 0u;
+            u[k] = lo | (hi << 16);
+        }
+    }
+    __device__ __forceinline__ void st_bf16(uint16_t* p, int n, const uint32_t (&u)[2]) const
+    {
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            if (2 * k < n) p[2 * k] = (uint16_t)(u[k] & 0xffffu);
+            if (2 * k + 1 < n) p[2 * k + 1] = (uint16_t)(u[k] >> 16);
+        }
+    }
+
+    __device__ __forceinline__ void load_g(int row, float (&v)[kVec]) const { ld_f32(a.g + flat(row), valid(row), v); }
+    __device__ __forceinline__ void load_mom(int row, float (&v)[kVec]) const { ld_f32(a.mom + flat(row), valid(row), v); }
+    __device__ __forceinline__ void store_g(int row, const float (&v)[kVec]) const { st_f32(a.g + flat(row), valid(row), v); }
+    __device__ __forceinline__ void store_mom(int row, const float (&v)[kVec]) const { st_f32(a.mom + flat(row), valid(row), v); }
+    __device__ __forceinline__ void load_ws(uint32_t m, int row, uint32_t (&u)[2]) const { ld_bf16(a.w_send[m] + flat(row), valid(row), u); }
+    __device__ __forceinline__ void load_wn(uint32_t m, int row, uint32_t (&u)[2]) const { ld_bf16(a.w_now[m] + flat(row), valid(row), u); }
+    __device__ __forceinline__ void store_wn(uint32_t m, int row, const uint32_t (&u)[2]) const { st_bf16(a.w_now[m] + flat(row), valid(row), u); }
+
+    template <int FMT> __device__ __forceinline__ void load_message(uint32_t m, int row, float (&dq)[kVec]) const
+    {
+        const uint8_t* codes = a.codes[m];
+        const uint64_t b = first(row);
+        const int n = valid(row);
+        if constexpr (FMT == SDL_FMT_FP32) {
+            ld_f32(reinterpret_cast<const float*>(codes) + b, n, dq);
+        } else if constexpr (FMT == SDL_FMT_BF16) {
+            uint32_t u[2];
+            ld_bf16(reinterpret_cast<const uint16_t*>(codes) + b, n, u);
+            unpack_bf16(u, dq);
+        } else {
+            const uint32_t sb = n > 0 ? a.scales[m][b / SDL_BLOCK] : 127u;
+            const float scale = scale_from_byte(sb);
+            uint32_t c0 = 0;
+            if constexpr (FMT == SDL_FMT_E3M0) {
+#pragma unroll
+                for (int k = 0; k < 2; ++k)
+                    if (2 * k < n) c0 |= (uint32_t)codes[b / 2 + k] << (8 * k);
+                decode_e3m0(c0, scale, dq);
             } else {
 #pragma unroll
-                for (int j = 0; j < kLane; ++j)
-                    if (j < valid) codes[base + j] = (uint8_t)((j < 4 ? c[0] : c[1]) >> (8 * (j & 3)));
+                for (int j = 0; j < kVec; ++j)
+                    if (j < n) c0 |= (uint32_t)codes[b + j] << (8 * j);
+                decode_e4m3(c0, scale, dq);
+            }
+        }
+    }
+    template <int FMT>
+    __device__ __forceinline__ void store_message(uint32_t m, int row, const uint32_t (&c)[kVec], uint32_t sb) const
+    {
+        uint8_t* codes = a.codes[m];
+        const uint64_t b = first(row);
+        const int n = valid(row);
+        if constexpr (FMT == SDL_FMT_FP32) {
+            float v[kVec];
+#pragma unroll
+            for (int j = 0; j < kVec; ++j) v[j] = u2f(c[j]);
+            st_f32(reinterpret_cast<float*>(codes) + b, n, v);
+        } else if constexpr (FMT == SDL_FMT_BF16) {
+            const uint32_t u[2] = {c[0], c[1]};
+            st_bf16(reinterpret_cast<uint16_t*>(codes) + b, n, u);
+        } else {
+            if ((lane % kBlockLanes) == 0u && n > 0) a.scales[m][b / SDL_BLOCK] = (uint8_t)sb;
+            if constexpr (FMT == SDL_FMT_E3M0) {
+                // elements beyond the end are zero outer gradients: their nibbles are 0
+#pragma unroll
+                for (int k = 0; k < 2; ++k)
+                    if (2 * k < n) codes[b / 2 + k] = (uint8_t)(c[0] >> (8 * k));
+            } else {
+#pragma unroll
+                for (int j = 0; j < kVec; ++j)
+                    if (j < n) codes[b + j] = (uint8_t)(c[0] >> (8 * j));
+            }
+        }
+    }
+};
+
+// ------------------------------------------------------------------ the arithmetic of one lane
+// MT > 0: number of replicas known at compile time; the replicas' words are loaded up
+// front so that many loads are in flight.  MT == 0: any M, one replica at a time.
+
+// ALIASED: w_send[m] and w_now[m] are the same array (no overlap delay).  EMIT: the fused
+// kernel also writes the messages.
+template <int MODE, int FMT, int MT, bool ALIASED, bool EMIT, class IO>
+__device__ __forceinline__ void process(const Args& a, const IO& io)
+{
+    const uint32_t M = MT > 0 ? (uint32_t)MT : a.M;
+    constexpr int MU = MT > 0 ? MT : 1;
+
+    float g[kRows][kVec], mom[kRows][kVec], acc[kRows][kVec];
+    uint32_t ws[MU][kRows][2], wn[MU][kRows][2];
+
+    // ---- loads that do not depend on anything
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        io.load_g(r, g[r]);
+        if constexpr (MODE == kReduce || MODE == kFused) io.load_mom(r, mom[r]);
+    }
+    if constexpr (MT > 0) {
+        if constexpr (MODE == kQuantize || MODE == kFused) {
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int r = 0; r < kRows; ++r) io.load_ws(m, r, ws[m][r]);
+        }
+        if constexpr (MODE == kMerge) {
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int r = 0; r < kRows; ++r) io.load_wn(m, r, wn[m][r]);
+        }
+        if constexpr (MODE == kFused && !ALIASED) {
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int r = 0; r < kRows; ++r) io.load_wn(m, r, wn[m][r]);
+        }
+    }
+
+    // ---- outer gradients, messages, fp32 sum over replicas in ascending order
+    if constexpr (MODE != kMerge) {
+#pragma unroll
+        for (int r = 0; r < kRows; ++r)
+#pragma unroll
+            for (int j = 0; j < kVec; ++j) acc[r][j] = 0.0f;
+#pragma unroll
+        for (uint32_t m = 0; m < M; ++m) {
+            const int mi = MT > 0 ? (int)m : 0;
+#pragma unroll
+            for (int r = 0; r < kRows; ++r) {
+                float dq[kVec];
+                if constexpr (MODE == kReduce) {
+                    io.template load_message<FMT>(m, r, dq);
+                } else {
+                    if constexpr (MT == 0) io.load_ws(m, r, ws[0][r]);
+                    float w[kVec], d[kVec];
+                    uint32_t c[kVec], sb;
+                    unpack_bf16(ws[mi][r], w);
+#pragma unroll
+                    for (int j = 0; j < kVec; ++j) d[j] = g[r][j] - w[j];
+                    constexpr bool want = MODE == kQuantize || EMIT;
+                    encode<FMT>(d, dq, c, sb, want);
+                    if constexpr (want) io.template store_message<FMT>(m, r, c, sb);
+                }
+#pragma unroll
+                for (int j = 0; j < kVec; ++j) acc[r][j] = acc[r][j] + dq[j];
+            }
+            // finish one replica before the next: keeps the live registers of the wide
+            // variants within the budget of SDL_WAVES_PER_EU
+            if constexpr (MT >= SDL_SERIALIZE_FROM) __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+
+    // ---- mean and Nesterov outer step
+    if constexpr (MODE == kReduce || MODE == kFused) {
+        const float fm = (float)M;
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) {
+#pragma unroll
+            for (int j = 0; j < kVec; ++j) {
+                const float dbar = acc[r][j] / fm;
+                const float m_new = a.mu * mom[r][j] + dbar;
+                const float look = dbar + a.mu * m_new;
+                mom[r][j] = m_new;
+                g[r][j] = g[r][j] - a.lr * look;
+            }
+            io.store_g(r, g[r]);
+            io.store_mom(r, mom[r]);
+        }
+    }
+
+    // ---- alpha-merge into every replica
+    if constexpr (MODE == kMerge || MODE == kFused) {
+#pragma unroll
+        for (uint32_t m = 0; m < M; ++m) {
+            const int mi = MT > 0 ? (int)m : 0;
+#pragma unroll
+            for (int r = 0; r < kRows; ++r) {
+                if constexpr (MT == 0) io.load_wn(m, r, wn[0][r]);
+                float w[kVec];
+                if constexpr (MT > 0 && MODE == kFused && ALIASED) {
+                    // same words as at the send step; hide that from the optimizer so that it
+                    // re-expands the two packed registers instead of keeping four floats alive
+                    uint32_t u[2] = {ws[mi][r][0], ws[mi][r][1]};
+                    asm volatile("" : "+v"(u[0]), "+v"(u[1]));
+                    unpack_bf16(u, w);
+                } else {
+                    unpack_bf16(wn[mi][r], w);
+                }
+                uint32_t out[2];
+#pragma unroll
+                for (int k = 0; k < 2; ++k)
+                    out[k] = bf16_pack(a.alpha * w[2 * k] + a.one_minus_alpha * g[r][2 * k],
+                                       a.alpha * w[2 * k + 1] + a.one_minus_alpha * g[r][2 * k + 1]);
+                io.store_wn(m, r, out);
             }
         }
     }
 }
 
 // ------------------------------------------------------------------ the kernel
-// MT > 0: number of replicas known at compile time, all loads issued up front.
-// MT == 0: any M, replicas visited in a run-time loop.
 
-template <int MODE, int FMT, int MT>
-__global__ __launch_bounds__(kThreads) void sdl_kernel(const Args a)
+template <int MODE, int FMT, int MT, bool ALIASED, bool EMIT>
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(SDL_WAVES_PER_EU)))
+void sdl_kernel(const Args a)
 {
     // which run does this workgroup work on (uniform scan of at most kMaxRuns entries)
     const uint32_t wg = blockIdx.x;
@@ -341,104 +587,22 @@ __global__ __launch_bounds__(kThreads) void sdl_kernel(const Args a)
         if (wg >= a.runs[i].first_wg) r = i;
     const uint64_t run_off = a.runs[r].offset;
     const uint64_t run_n = a.runs[r].numel;
-    const uint64_t base = ((uint64_t)(wg - a.runs[r].first_wg) * kThreads + threadIdx.x) * kLane;
-    const int valid = base >= run_n ? 0 : (run_n - base >= (uint64_t)kLane ? kLane : (int)(run_n - base));
-    const bool fast = a.runs[r].vec && valid == kLane;
-    const uint64_t e0 = run_off + base;           // index into the flat model arrays
-    const uint32_t M = MT > 0 ? (uint32_t)MT : a.M;
-    constexpr int MU = MT > 0 ? MT : 1;
-
-    float g[kLane], mom[kLane], acc[kLane];
-    uint32_t ws[MU][4], wn[MU][4];
-
-    // ---- loads that do not depend on anything
-    load_f32(a.g + e0, valid, fast, g);
-    if constexpr (MODE == kReduce || MODE == kFused) load_f32(a.mom + e0, valid, fast, mom);
-    if constexpr (MT > 0) {
-        if constexpr (MODE == kQuantize || MODE == kFused) {
-#pragma unroll
-            for (int m = 0; m < MT; ++m) load_bf16(a.w_send[m] + e0, valid, fast, ws[m]);
-        }
-        if constexpr (MODE == kMerge) {
-#pragma unroll
-            for (int m = 0; m < MT; ++m) load_bf16(a.w_now[m] + e0, valid, fast, wn[m]);
-        }
-        if constexpr (MODE == kFused) {
-            if (!a.aliased) {
-#pragma unroll
-                for (int m = 0; m < MT; ++m) load_bf16(a.w_now[m] + e0, valid, fast, wn[m]);
-            }
-        }
-    }
-
-    // ---- outer gradients, messages, fp32 sum over replicas in ascending order
-    if constexpr (MODE != kMerge) {
-#pragma unroll
-        for (int j = 0; j < kLane; ++j) acc[j] = 0.0f;
-#pragma unroll
-        for (uint32_t m = 0; m < M; ++m) {
-            float dq[kLane];
-            if constexpr (MODE == kReduce) {
-                load_decode<FMT>(a.codes[m], a.scales[m], base, valid, fast, dq);
-            } else {
-                const int mi = MT > 0 ? (int)m : 0;
-                if constexpr (MT == 0) load_bf16(a.w_send[m] + e0, valid, fast, ws[0]);
-                float w[kLane], d[kLane];
-                uint32_t c[kLane], sb;
-                unpack_bf16(ws[mi], w);
-#pragma unroll
-                for (int j = 0; j < kLane; ++j) d[j] = g[j] - w[j];
-                const bool want = MODE == kQuantize || a.emit;
-                encode<FMT>(d, dq, c, sb, want);
-                if (want) store_codes<FMT>(a.codes[m], a.scales[m], base, valid, fast, c, sb);
-            }
-#pragma unroll
-            for (int j = 0; j < kLane; ++j) acc[j] = acc[j] + dq[j];
-        }
-    }
-
-    // ---- mean and Nesterov outer step
-    if constexpr (MODE == kReduce || MODE == kFused) {
-        const float fm = (float)M;
-#pragma unroll
-        for (int j = 0; j < kLane; ++j) {
-            const float dbar = acc[j] / fm;
-            const float m_new = a.mu * mom[j] + dbar;
-            const float look = dbar + a.mu * m_new;
-            mom[j] = m_new;
-            g[j] = g[j] - a.lr * look;
-        }
-        store_f32(a.g + e0, valid, fast, g);
-        store_f32(a.mom + e0, valid, fast, mom);
-    }
-
-    // ---- alpha-merge into every replica
-    if constexpr (MODE == kMerge || MODE == kFused) {
-        float gpart[kLane];
-#pragma unroll
-        for (int j = 0; j < kLane; ++j) gpart[j] = a.one_minus_alpha * g[j];
-#pragma unroll
-        for (uint32_t m = 0; m < M; ++m) {
-            const int mi = MT > 0 ? (int)m : 0;
-            if constexpr (MT == 0) load_bf16(a.w_now[m] + e0, valid, fast, wn[0]);
-            float w[kLane];
-            if (MT > 0 && MODE == kFused && a.aliased) unpack_bf16(ws[mi], w);
-            else unpack_bf16(wn[mi], w);
-            uint32_t out[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k)
-                out[k] = bf16_pack(a.alpha * w[2 * k] + gpart[2 * k],
-                                   a.alpha * w[2 * k + 1] + gpart[2 * k + 1]);
-            store_bf16(a.w_now[m] + e0, valid, fast, out);
-        }
+    const uint64_t tile = (uint64_t)(wg - a.runs[r].first_wg) * kGroup;   // first element of the tile in the run
+    if (a.runs[r].vec && run_n - tile >= (uint64_t)kGroup) {
+        const TileIO io{a, run_off + tile, tile, threadIdx.x};
+        process<MODE, FMT, MT, ALIASED, EMIT>(a, io);
+    } else {
+        const GuardedIO io{a, run_off + tile, tile, run_n, threadIdx.x};
+        process<MODE, FMT, 0, ALIASED, EMIT>(a, io);
     }
 }
 
 // Plain streaming copy, 16 bytes per lane: the yardstick for the HBM roofline.
-__global__ __launch_bounds__(kThreads) void sdl_copy_kernel(uint4* __restrict__ dst,
+constexpr int kCopyThreads = 256;
+__global__ __launch_bounds__(kCopyThreads) void sdl_copy_kernel(uint4* __restrict__ dst,
                                                             const uint4* __restrict__ src, uint64_t n16)
 {
-    const uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+    const uint64_t i = (uint64_t)blockIdx.x * kCopyThreads + threadIdx.x;
     if (i < n16) dst[i] = src[i];
 }
 
@@ -461,29 +625,42 @@ size_t code_bytes_at(sdl_format_t fmt, uint64_t elem)
     }
 }
 
-template <int MODE, int FMT>
+template <int MODE, int FMT, bool ALIASED, bool EMIT>
 hipError_t launch_m(const Args& a, uint32_t n_wg, hipStream_t s)
 {
-    const dim3 grid(n_wg), block(kThreads);
-    switch (a.M) {
-    case 1: hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 1>), grid, block, 0, s, a); break;
-    case 2: hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 2>), grid, block, 0, s, a); break;
-    case 4: hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 4>), grid, block, 0, s, a); break;
-    case 8: hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 8>), grid, block, 0, s, a); break;
-    default: hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 0>), grid, block, 0, s, a); break;
+    const dim3 grid(n_wg), block(kWave);
+    // the message-writing fused kernel is a verification aid: one generic-M variant is enough
+    const uint32_t mt = (MODE == kFused && EMIT) ? 0u : a.M;
+    switch (mt) {
+    case 1: if constexpr (!EMIT) hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 1, ALIASED, EMIT>), grid, block, SDL_LDS_BYTES, s, a); break;
+    case 2: if constexpr (!EMIT) hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 2, ALIASED, EMIT>), grid, block, SDL_LDS_BYTES, s, a); break;
+    case 4: if constexpr (!EMIT) hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 4, ALIASED, EMIT>), grid, block, SDL_LDS_BYTES, s, a); break;
+    case 8: if constexpr (!EMIT) hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 8, ALIASED, EMIT>), grid, block, SDL_LDS_BYTES, s, a); break;
+    default: hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 0, ALIASED, EMIT>), grid, block, SDL_LDS_BYTES, s, a); break;
     }
     return hipGetLastError();
+}
+
+template <int MODE, int FMT>
+hipError_t launch_f(const Args& a, uint32_t n_wg, hipStream_t s)
+{
+    if constexpr (MODE == kFused) {
+        if (a.emit) return a.aliased ? launch_m<MODE, FMT, true, true>(a, n_wg, s) : launch_m<MODE, FMT, false, true>(a, n_wg, s);
+        return a.aliased ? launch_m<MODE, FMT, true, false>(a, n_wg, s) : launch_m<MODE, FMT, false, false>(a, n_wg, s);
+    } else {
+        return launch_m<MODE, FMT, false, false>(a, n_wg, s);
+    }
 }
 
 template <int MODE>
 hipError_t launch(const Args& a, sdl_format_t fmt, uint32_t n_wg, hipStream_t s)
 {
-    if constexpr (MODE == kMerge) return launch_m<MODE, SDL_FMT_FP32>(a, n_wg, s);
+    if constexpr (MODE == kMerge) return launch_f<MODE, SDL_FMT_FP32>(a, n_wg, s);
     switch (fmt) {
-    case SDL_FMT_FP32: return launch_m<MODE, SDL_FMT_FP32>(a, n_wg, s);
-    case SDL_FMT_BF16: return launch_m<MODE, SDL_FMT_BF16>(a, n_wg, s);
-    case SDL_FMT_E4M3: return launch_m<MODE, SDL_FMT_E4M3>(a, n_wg, s);
-    default: return launch_m<MODE, SDL_FMT_E3M0>(a, n_wg, s);
+    case SDL_FMT_FP32: return launch_f<MODE, SDL_FMT_FP32>(a, n_wg, s);
+    case SDL_FMT_BF16: return launch_f<MODE, SDL_FMT_BF16>(a, n_wg, s);
+    case SDL_FMT_E4M3: return launch_f<MODE, SDL_FMT_E4M3>(a, n_wg, s);
+    default: return launch_f<MODE, SDL_FMT_E3M0>(a, n_wg, s);
     }
 }
 
@@ -666,9 +843,9 @@ int sdl_copy_bytes(void* dst, const void* src, uint64_t nbytes, void* stream)
     if (nbytes == 0) return SDL_OK;
     if (!dst || !src || nbytes % 16 != 0) return SDL_ERR_INVALID_ARG;
     if (!aligned(dst, 16) || !aligned(src, 16)) return SDL_ERR_ALIGNMENT;
-    const uint64_t n16 = nbytes / 16, n_wg = (n16 + kThreads - 1) / kThreads;
+    const uint64_t n16 = nbytes / 16, n_wg = (n16 + kCopyThreads - 1) / kCopyThreads;
     if (n_wg > 0x7fffffffull) return SDL_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(sdl_copy_kernel, dim3((uint32_t)n_wg), dim3(kThreads), 0, (hipStream_t)stream,
+    hipLaunchKernelGGL(sdl_copy_kernel, dim3((uint32_t)n_wg), dim3(kCopyThreads), 0, (hipStream_t)stream,
                        static_cast<uint4*>(dst), static_cast<const uint4*>(src), n16);
     return hipGetLastError() == hipSuccess ? SDL_OK : SDL_ERR_DEVICE;
 }

@@ -90,9 +90,9 @@ def test_config_4b_p1_equals_p6(fmt):
     wl1 = workloads.WORKLOADS["4b_p1"]
     wl6 = workloads.WORKLOADS["4b_p6"]
     one = FlatModel(wl1)
-    assert one.plan.total_numel == 4273695744 > 2 ** 32
+    assert one.plan.total_numel == 4273695744 > 2 ** 31        # 32-bit element indices overflow
     wins = one.windows(0, n_random=12, seed=4)
-    # make sure the tail of the flat arrays (beyond 2^32 elements) is sampled
+    # make sure the tail of the flat arrays (beyond 2^31 elements, byte offsets beyond 2^34) is sampled
     assert max(o + n for o, n in wins) == one.plan.total_numel
     snaps = one.snapshot(wins)
     print("4b P=1 step", flush=True)
