@@ -23,6 +23,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <cstdlib>
 #include <cstring>
 
 #include "sdl.h"
@@ -74,9 +75,6 @@ struct Args {
 #endif
 #ifndef SDL_WAVES_PER_EU
 #define SDL_WAVES_PER_EU 2   // register budget: at least this many wavefronts per SIMD
-#endif
-#ifndef SDL_LDS_BYTES
-#define SDL_LDS_BYTES 0      // dynamic LDS requested per workgroup, only to cap the wavefronts per CU
 #endif
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -625,18 +623,35 @@ size_t code_bytes_at(sdl_format_t fmt, uint64_t elem)
     }
 }
 
+// Dynamic LDS requested per workgroup.  The kernels use no LDS; the request only caps how
+// many wavefronts share a CU (160 KiB of LDS per CU), which is the knob that matters for a
+// streaming kernel: enough loads in flight, not so many that the access window in each
+// array grows and DRAM page locality is lost.  Measured on MI355X: the fused kernel with
+// a compile-time replica count is fastest at 8 wavefronts per CU (12 when w_send aliases
+// w_now); the other kernels want every wavefront they can get.
+// SDL_TUNE_LDS_BYTES in the environment overrides the choice (tuning aid).
+uint32_t lds_cap_bytes(int mode, uint32_t mt, bool aliased)
+{
+    static const int env = [] { const char* e = std::getenv("SDL_TUNE_LDS_BYTES"); return e ? std::atoi(e) : -1; }();
+    if (env >= 0) return (uint32_t)env;
+    if (mode == kFused && mt > 0) return aliased ? 13653u : 20480u;
+    return 0u;
+}
+
 template <int MODE, int FMT, bool ALIASED, bool EMIT>
 hipError_t launch_m(const Args& a, uint32_t n_wg, hipStream_t s)
 {
     const dim3 grid(n_wg), block(kWave);
     // the message-writing fused kernel is a verification aid: one generic-M variant is enough
-    const uint32_t mt = (MODE == kFused && EMIT) ? 0u : a.M;
+    uint32_t mt = (MODE == kFused && EMIT) ? 0u : a.M;
+    if (mt != 1 && mt != 2 && mt != 4 && mt != 8) mt = 0;
+    const uint32_t lds = lds_cap_bytes(MODE, mt, ALIASED);
     switch (mt) {
-    case 1: if constexpr (!EMIT) hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 1, ALIASED, EMIT>), grid, block, SDL_LDS_BYTES, s, a); break;
-    case 2: if constexpr (!EMIT) hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 2, ALIASED, EMIT>), grid, block, SDL_LDS_BYTES, s, a); break;
-    case 4: if constexpr (!EMIT) hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 4, ALIASED, EMIT>), grid, block, SDL_LDS_BYTES, s, a); break;
-    case 8: if constexpr (!EMIT) hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 8, ALIASED, EMIT>), grid, block, SDL_LDS_BYTES, s, a); break;
-    default: hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 0, ALIASED, EMIT>), grid, block, SDL_LDS_BYTES, s, a); break;
+    case 1: if constexpr (!EMIT) hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 1, ALIASED, EMIT>), grid, block, lds, s, a); break;
+    case 2: if constexpr (!EMIT) hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 2, ALIASED, EMIT>), grid, block, lds, s, a); break;
+    case 4: if constexpr (!EMIT) hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 4, ALIASED, EMIT>), grid, block, lds, s, a); break;
+    case 8: if constexpr (!EMIT) hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 8, ALIASED, EMIT>), grid, block, lds, s, a); break;
+    default: hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 0, ALIASED, EMIT>), grid, block, lds, s, a); break;
     }
     return hipGetLastError();
 }
