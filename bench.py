@@ -29,7 +29,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 DEFAULT_FRAGMENT = {"tiny": 0, "100m": 1, "1b": 1, "4b_p6": 1, "4b_p1": 0, "stress": 1}
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by
 # the reading of the copy kernel); see profiles/.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/fused_e3m0_1b_m4_hbm_traffic.txt: 7.2478e9 B fetched + 4.8323e9 B written per launch
+    ("1b", 4, "e3m0"): 12.0801e9,
+}
 
 
 def algorithmic_bytes_per_param(M: int, tau: int) -> float:
