@@ -11,7 +11,8 @@
  *   or fused       sdl_fragment_outer_step       all of the above in one pass
  *
  * and sdl_fragment_plan builds the fragment map and the send/receive schedule on
- * the host.  The M replicas ("workers") are M parameter arrays resident in one
+ * the host; the *_plan forms of the calls work on whole fragments of a plan, and
+ * sdl_engine_step drives them along the schedule.  The M replicas ("workers") are M parameter arrays resident in one
  * GPU's memory; no call communicates with another device.
  *
  * Conventions for every call
@@ -184,6 +185,49 @@ int sdl_fragment_outer_step(float* g, float* mom, const void* const* w_send, voi
 int sdl_fragment_outer_step_plan(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
                                  const void* const* w_send_base, void* const* w_now_base, uint32_t M,
                                  sdl_format_t fmt, float lr, float mu, float alpha, void* stream);
+
+/* Fragment-level forms of the send-side and receive-side calls: every run of fragment p
+ * of a plan, on the flat model arrays (bases = element 0 of the model).  The messages of a
+ * fragment are laid out as the concatenation of its runs, each run padded to a multiple
+ * of 512 elements; sdl_plan_message_bytes gives the size of codes[m] / scales[m] for that
+ * layout.  Argument meaning, arithmetic and errors as in the span-level calls above. */
+int sdl_plan_message_bytes(const sdl_plan_t* plan, uint32_t p, sdl_format_t fmt, size_t* code_bytes,
+                           size_t* scale_bytes);
+int sdl_quantize_outer_grad_plan(const sdl_plan_t* plan, uint32_t p, const float* g_base,
+                                 const void* const* w_send_base, uint32_t M, sdl_format_t fmt,
+                                 void* const* codes, void* const* scales, void* stream);
+int sdl_dequant_reduce_nesterov_plan(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
+                                     const void* const* codes, const void* const* scales, uint32_t M,
+                                     sdl_format_t fmt, float lr, float mu, void* stream);
+int sdl_merge_overlap_plan(const sdl_plan_t* plan, uint32_t p, const float* g_new_base, void* const* w_now_base,
+                           uint32_t M, float alpha, void* stream);
+
+/* ------------------------------------------------------------------ schedule driver
+ *
+ * Algorithm 2 as a whole, seen from the outer optimizer: the caller runs the inner steps
+ * (its own training code updates the M replicas in place) and calls sdl_engine_step(t)
+ * after the inner update of step t = 1, 2, ...  The engine issues, on `stream`,
+ *   - for every fragment that sends at t (t = t_p + k*H): sdl_quantize_outer_grad_plan into
+ *     that fragment's message buffers (the exchange between workers would happen here);
+ *   - tau steps later: sdl_dequant_reduce_nesterov_plan, then sdl_merge_overlap_plan into
+ *     the replicas as they are then (Section 2.3);
+ *   - with tau = 0 for every worker: sdl_fragment_outer_step_plan at the send step.
+ * tau_m[m] < H is worker m's delay (Section 3.3.2: workers may receive the same update at
+ * different steps); the mean and the Nesterov update happen once, at the smallest delay,
+ * and each worker merges when its own delay expires.
+ * The plan must outlive the engine.  H must be the H the plan was built with.  Steps must
+ * be fed in order without gaps (a skipped receive is reported as SDL_ERR_INVALID_ARG).
+ * sdl_engine_bind: g_base, mom_base, w_base[M] = flat device arrays (the live replicas);
+ * codes / scales = host arrays of P*M device pointers, entry p*M + m sized by
+ * sdl_plan_message_bytes(plan, p, ...); both may be NULL when every delay is 0.
+ * n_sent / n_received (optional) count the fragments whose send / mean+Nesterov ran. */
+typedef struct sdl_engine sdl_engine_t;
+int sdl_engine_create(const sdl_plan_t* plan, uint32_t H, uint32_t M, const uint32_t* tau_m, sdl_format_t fmt,
+                      float lr, float mu, float alpha, sdl_engine_t** out);
+void sdl_engine_destroy(sdl_engine_t* engine);
+int sdl_engine_bind(sdl_engine_t* engine, float* g_base, float* mom_base, void* const* w_base,
+                    void* const* codes, void* const* scales);
+int sdl_engine_step(sdl_engine_t* engine, uint64_t t, void* stream, uint32_t* n_sent, uint32_t* n_received);
 
 /* Plain device-to-device streaming copy of nbytes (a multiple of 16; both pointers
  * 16-byte aligned).  Not part of the method: it is the yardstick against which the

@@ -188,3 +188,6 @@ def unpack_e3m0(codes: np.ndarray, n: int) -> np.ndarray:
     """Packed nibbles -> one code per element (pure re-indexing, for test read-outs)."""
     lo, hi = codes & 15, codes >> 4
     return np.stack([lo, hi], axis=1).reshape(-1)[:n]
+
+
+from .engine import RefEngine  # noqa: E402,F401

@@ -67,6 +67,17 @@ def _load() -> ctypes.CDLL:
                                             pp, pp, vp]
     lib.sdl_fragment_outer_step_plan.argtypes = [vp, u32, vp, vp, pp, pp, u32, ctypes.c_int, f32, f32,
                                                  f32, vp]
+    lib.sdl_plan_message_bytes.argtypes = [vp, u32, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t),
+                                           ctypes.POINTER(ctypes.c_size_t)]
+    lib.sdl_quantize_outer_grad_plan.argtypes = [vp, u32, vp, pp, u32, ctypes.c_int, pp, pp, vp]
+    lib.sdl_dequant_reduce_nesterov_plan.argtypes = [vp, u32, vp, vp, pp, pp, u32, ctypes.c_int, f32, f32, vp]
+    lib.sdl_merge_overlap_plan.argtypes = [vp, u32, vp, pp, u32, f32, vp]
+    lib.sdl_engine_create.argtypes = [vp, u32, u32, ctypes.POINTER(u32), ctypes.c_int, f32, f32, f32,
+                                      ctypes.POINTER(vp)]
+    lib.sdl_engine_destroy.argtypes = [vp]
+    lib.sdl_engine_destroy.restype = None
+    lib.sdl_engine_bind.argtypes = [vp, vp, vp, pp, pp, pp]
+    lib.sdl_engine_step.argtypes = [vp, u64, vp, ctypes.POINTER(u32), ctypes.POINTER(u32)]
     lib.sdl_copy_bytes.argtypes = [vp, vp, u64, vp]
     lib.sdl_status_string.argtypes = [ctypes.c_int]
     lib.sdl_status_string.restype = ctypes.c_char_p
@@ -237,6 +248,73 @@ def sdl_fragment_outer_step_plan(plan: Plan, p: int, g_base, mom_base, w_send_ba
                                              _ptr_array(w_send_base), _ptr_array(w_now_base),
                                              len(w_send_base), fmt, lr, mu, alpha, _stream(stream)),
            "sdl_fragment_outer_step_plan")
+
+
+def sdl_plan_message_bytes(plan: Plan, p: int, fmt: int) -> Tuple[int, int]:
+    c, s = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(_lib.sdl_plan_message_bytes(plan._h, p, fmt, ctypes.byref(c), ctypes.byref(s)),
+           "sdl_plan_message_bytes")
+    return c.value, s.value
+
+
+def sdl_quantize_outer_grad_plan(plan: Plan, p: int, g_base, w_send_base, fmt: int, codes, scales=None,
+                                 stream=None):
+    _require_device(g_base, *w_send_base, *codes, *(scales or []))
+    _check(_lib.sdl_quantize_outer_grad_plan(plan._h, p, _ptr(g_base), _ptr_array(w_send_base),
+                                             len(w_send_base), fmt, _ptr_array(codes), _ptr_array(scales),
+                                             _stream(stream)), "sdl_quantize_outer_grad_plan")
+
+
+def sdl_dequant_reduce_nesterov_plan(plan: Plan, p: int, g_base, mom_base, codes, scales, fmt: int, lr: float,
+                                     mu: float, stream=None):
+    _require_device(g_base, mom_base, *codes, *(scales or []))
+    _check(_lib.sdl_dequant_reduce_nesterov_plan(plan._h, p, _ptr(g_base), _ptr(mom_base), _ptr_array(codes),
+                                                 _ptr_array(scales), len(codes), fmt, lr, mu, _stream(stream)),
+           "sdl_dequant_reduce_nesterov_plan")
+
+
+def sdl_merge_overlap_plan(plan: Plan, p: int, g_new_base, w_now_base, alpha: float, stream=None):
+    _require_device(g_new_base, *w_now_base)
+    _check(_lib.sdl_merge_overlap_plan(plan._h, p, _ptr(g_new_base), _ptr_array(w_now_base), len(w_now_base),
+                                       alpha, _stream(stream)), "sdl_merge_overlap_plan")
+
+
+class Engine:
+    """Owner of an sdl_engine_t handle (keeps the plan and the bound tensors alive)."""
+
+    def __init__(self, handle: int, plan: Plan):
+        self._h = ctypes.c_void_p(handle)
+        self._plan = plan
+        self._keep = None
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.sdl_engine_destroy(self._h)
+            self._h = None
+
+
+def sdl_engine_create(plan: Plan, H: int, tau_m: Sequence[int], fmt: int, lr: float, mu: float,
+                      alpha: float) -> Engine:
+    taus = (ctypes.c_uint32 * len(tau_m))(*tau_m)
+    out = ctypes.c_void_p()
+    _check(_lib.sdl_engine_create(plan._h, H, len(tau_m), taus, fmt, lr, mu, alpha, ctypes.byref(out)),
+           "sdl_engine_create")
+    return Engine(out.value, plan)
+
+
+def sdl_engine_bind(engine: Engine, g_base, mom_base, w_base, codes=None, scales=None):
+    """codes / scales: flat lists of P*M tensors, entry p*M + m."""
+    _require_device(g_base, mom_base, *w_base, *(codes or []), *(scales or []))
+    _check(_lib.sdl_engine_bind(engine._h, _ptr(g_base), _ptr(mom_base), _ptr_array(w_base), _ptr_array(codes),
+                                _ptr_array(scales)), "sdl_engine_bind")
+    engine._keep = (g_base, mom_base, list(w_base), codes, scales)
+
+
+def sdl_engine_step(engine: Engine, t: int, stream=None) -> Tuple[int, int]:
+    ns, nr = ctypes.c_uint32(), ctypes.c_uint32()
+    _check(_lib.sdl_engine_step(engine._h, t, _stream(stream), ctypes.byref(ns), ctypes.byref(nr)),
+           "sdl_engine_step")
+    return ns.value, nr.value
 
 
 def sdl_copy_bytes(dst, src, nbytes: int, stream=None):

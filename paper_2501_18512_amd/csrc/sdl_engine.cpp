@@ -1,0 +1,153 @@
+// Host-side driver of Algorithm 2's outer-optimization schedule: at every inner step it
+// issues the send-side and receive-side calls of the fragments that are due (Section 2.2:
+// staggered fragments; Section 2.3: the result of a send is consumed tau steps later, with
+// an optional different delay per worker, Section 3.3.2 "slack between workers").
+// Uses only the plan-level entry points of sdl.h; no device code here.
+#include <new>
+#include <vector>
+
+#include "sdl.h"
+
+struct sdl_engine {
+    const sdl_plan_t* plan = nullptr;
+    uint32_t P = 0, M = 0, H = 0;
+    sdl_format_t fmt = SDL_FMT_E3M0;
+    float lr = 0, mu = 0, alpha = 0;
+    std::vector<uint32_t> offset;        // t_p
+    std::vector<uint32_t> delay;         // tau_m per worker
+    uint32_t delay_min = 0, delay_max = 0;
+    // bound memory
+    float* g = nullptr;
+    float* mom = nullptr;
+    std::vector<void*> w;                // M live replicas
+    std::vector<void*> codes, scales;    // P*M message buffers (index p*M + m); unused when all delays are 0
+    bool bound = false;
+    // per fragment: step at which the message in flight was sent (0 = none), reduce done?, merged[m]
+    std::vector<uint64_t> sent_at;
+    std::vector<uint8_t> reduced;
+    std::vector<uint8_t> merged;         // P*M
+};
+
+extern "C" {
+
+int sdl_engine_create(const sdl_plan_t* plan, uint32_t H, uint32_t M, const uint32_t* tau_m, sdl_format_t fmt,
+                      float lr, float mu, float alpha, sdl_engine_t** out)
+{
+    if (!plan || !out || !tau_m || M == 0 || M > SDL_MAX_WORKERS || H == 0) return SDL_ERR_INVALID_ARG;
+    if (fmt < SDL_FMT_FP32 || fmt > SDL_FMT_E3M0) return SDL_ERR_INVALID_ARG;
+    for (uint32_t m = 0; m < M; ++m)
+        if (tau_m[m] >= H) return SDL_ERR_INVALID_ARG;
+    sdl_engine* e = nullptr;
+    try {
+        e = new sdl_engine();
+        e->plan = plan; e->P = sdl_plan_num_fragments(plan); e->M = M; e->H = H; e->fmt = fmt;
+        e->lr = lr; e->mu = mu; e->alpha = alpha;
+        e->offset.resize(e->P);
+        for (uint32_t p = 0; p < e->P; ++p) {
+            int rc = sdl_plan_offset(plan, p, &e->offset[p]);
+            if (rc != SDL_OK || e->offset[p] >= H) { delete e; return SDL_ERR_INVALID_ARG; }
+        }
+        e->delay.assign(tau_m, tau_m + M);
+        e->delay_min = e->delay_max = tau_m[0];
+        for (uint32_t m = 1; m < M; ++m) {
+            if (tau_m[m] < e->delay_min) e->delay_min = tau_m[m];
+            if (tau_m[m] > e->delay_max) e->delay_max = tau_m[m];
+        }
+        e->w.assign(M, nullptr);
+        e->codes.assign((size_t)e->P * M, nullptr);
+        e->scales.assign((size_t)e->P * M, nullptr);
+        e->sent_at.assign(e->P, 0);
+        e->reduced.assign(e->P, 0);
+        e->merged.assign((size_t)e->P * M, 0);
+    } catch (const std::bad_alloc&) {
+        delete e;
+        return SDL_ERR_NOMEM;
+    }
+    *out = e;
+    return SDL_OK;
+}
+
+void sdl_engine_destroy(sdl_engine_t* e) { delete e; }
+
+int sdl_engine_bind(sdl_engine_t* e, float* g_base, float* mom_base, void* const* w_base, void* const* codes,
+                    void* const* scales)
+{
+    if (!e || !g_base || !mom_base || !w_base) return SDL_ERR_INVALID_ARG;
+    const bool need_messages = e->delay_max > 0;
+    const bool scaled = e->fmt == SDL_FMT_E4M3 || e->fmt == SDL_FMT_E3M0;
+    if (need_messages && (!codes || (scaled && !scales))) return SDL_ERR_INVALID_ARG;
+    for (uint32_t m = 0; m < e->M; ++m)
+        if (!w_base[m]) return SDL_ERR_INVALID_ARG;
+    if (need_messages)
+        for (size_t i = 0; i < (size_t)e->P * e->M; ++i)
+            if (!codes[i] || (scaled && !scales[i])) return SDL_ERR_INVALID_ARG;
+    e->g = g_base; e->mom = mom_base;
+    for (uint32_t m = 0; m < e->M; ++m) e->w[m] = w_base[m];
+    for (size_t i = 0; i < (size_t)e->P * e->M; ++i) {
+        e->codes[i] = need_messages ? codes[i] : nullptr;
+        e->scales[i] = (need_messages && scaled) ? scales[i] : nullptr;
+    }
+    e->bound = true;
+    return SDL_OK;
+}
+
+int sdl_engine_step(sdl_engine_t* e, uint64_t t, void* stream, uint32_t* n_sent, uint32_t* n_received)
+{
+    if (!e || !e->bound || t == 0) return SDL_ERR_INVALID_ARG;
+    uint32_t sent = 0, received = 0;
+    const uint32_t M = e->M;
+    for (uint32_t p = 0; p < e->P; ++p) {
+        void* const* codes = e->codes.data() + (size_t)p * M;
+        void* const* scales = e->scales.data() + (size_t)p * M;
+        // ---- send side: t = t_p + k*H, k >= 1
+        const uint64_t s0 = e->offset[p];
+        if (t > s0 && (t - s0) % e->H == 0) {
+            if (e->sent_at[p] != 0) return SDL_ERR_INVALID_ARG;      // previous message not consumed: steps skipped
+            if (e->delay_max == 0) {
+                // no overlap anywhere: the whole outer step at once
+                int rc = sdl_fragment_outer_step_plan(e->plan, p, e->g, e->mom, e->w.data(), e->w.data(), M, e->fmt,
+                                                      e->lr, e->mu, e->alpha, stream);
+                if (rc != SDL_OK) return rc;
+                ++sent; ++received;
+                continue;
+            }
+            int rc = sdl_quantize_outer_grad_plan(e->plan, p, e->g, e->w.data(), M, e->fmt, codes, scales, stream);
+            if (rc != SDL_OK) return rc;
+            e->sent_at[p] = t;
+            e->reduced[p] = 0;
+            for (uint32_t m = 0; m < M; ++m) e->merged[(size_t)p * M + m] = 0;
+            ++sent;
+        }
+        // ---- receive side of the message in flight
+        if (e->sent_at[p] != 0) {
+            const uint64_t ts = e->sent_at[p];
+            if (!e->reduced[p] && t == ts + e->delay_min) {
+                int rc = sdl_dequant_reduce_nesterov_plan(e->plan, p, e->g, e->mom, codes, scales, M, e->fmt, e->lr,
+                                                          e->mu, stream);
+                if (rc != SDL_OK) return rc;
+                e->reduced[p] = 1;
+                ++received;
+            }
+            // merge into every worker whose delay expires now (one launch for all of them)
+            void* due[SDL_MAX_WORKERS];
+            uint32_t n_due = 0, n_done = 0;
+            for (uint32_t m = 0; m < M; ++m) {
+                uint8_t& done = e->merged[(size_t)p * M + m];
+                if (!done && t == ts + e->delay[m]) { due[n_due++] = e->w[m]; done = 1; }
+                n_done += done;
+            }
+            if (n_due) {
+                if (!e->reduced[p]) return SDL_ERR_INVALID_ARG;
+                int rc = sdl_merge_overlap_plan(e->plan, p, e->g, due, n_due, e->alpha, stream);
+                if (rc != SDL_OK) return rc;
+            }
+            if (n_done == M) e->sent_at[p] = 0;
+            else if (t > ts + e->delay_max) return SDL_ERR_INVALID_ARG;   // steps were skipped
+        }
+    }
+    if (n_sent) *n_sent = sent;
+    if (n_received) *n_received = received;
+    return SDL_OK;
+}
+
+}  // extern "C"

@@ -43,6 +43,7 @@ enum Mode { kQuantize = 0, kReduce = 1, kMerge = 2, kFused = 3 };
 struct Run {
     uint64_t offset;     // first element of the run in the flat arrays
     uint64_t numel;
+    uint64_t msg;        // where the run starts in the message arrays, in elements (a multiple of 512)
     uint32_t first_wg;   // first workgroup of the launch that works on this run
     uint32_t vec;        // 1: every array of this run is 16-byte aligned at its start
 };
@@ -68,6 +69,9 @@ struct Args {
 #endif
 #ifndef SDL_AUX_ST
 #define SDL_AUX_ST 2         // stores: non-temporal
+#endif
+#ifndef SDL_AUX_SCALE
+#define SDL_AUX_SCALE 0      // scale bytes: 16 per tile, 8 tiles per cache line -> let L2 combine them
 #endif
 
 #ifndef SDL_SERIALIZE_FROM
@@ -244,7 +248,7 @@ __device__ __forceinline__ void decode_e4m3(uint32_t c0, float scale, float (&dq
 struct TileIO {
     const Args& a;
     uint64_t t0;      // tile's first element in the flat arrays (workgroup uniform)
-    uint64_t tb;      // tile's first element counted from the run start (a multiple of 512)
+    uint64_t tb;      // tile's first element in the message arrays (a multiple of 512)
     uint32_t lane;
 
     static __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* p, uint32_t bytes)
@@ -297,7 +301,7 @@ struct TileIO {
         } else {
             const uint32_t sb = __builtin_amdgcn_raw_buffer_load_b8(
                 rsrc(a.scales[m] + tb / SDL_BLOCK, kGroup / SDL_BLOCK),
-                (int)(row * (kRow / SDL_BLOCK) + lane / kBlockLanes), 0, SDL_AUX_LD);
+                (int)(row * (kRow / SDL_BLOCK) + lane / kBlockLanes), 0, SDL_AUX_SCALE);
             const float scale = scale_from_byte(sb);
             if constexpr (FMT == SDL_FMT_E3M0) {
                 const uint32_t c0 = __builtin_amdgcn_raw_buffer_load_b16(rsrc(codes + tb / 2, kGroup / 2),
@@ -326,7 +330,7 @@ struct TileIO {
         } else {
             if ((lane % kBlockLanes) == 0u)
                 __builtin_amdgcn_raw_buffer_store_b8((uint8_t)sb, rsrc(a.scales[m] + tb / SDL_BLOCK, kGroup / SDL_BLOCK),
-                                                     (int)(row * (kRow / SDL_BLOCK) + lane / kBlockLanes), 0, SDL_AUX_ST);
+                                                     (int)(row * (kRow / SDL_BLOCK) + lane / kBlockLanes), 0, SDL_AUX_SCALE);
             if constexpr (FMT == SDL_FMT_E3M0) {
                 __builtin_amdgcn_raw_buffer_store_b16((uint16_t)c[0], rsrc(codes + tb / 2, kGroup / 2),
                                                       (int)(row * (kRow / 2) + lane * 2), 0, SDL_AUX_ST);
@@ -342,6 +346,7 @@ struct GuardedIO {
     const Args& a;
     uint64_t t0;           // tile's first element in the flat arrays
     uint64_t tb;           // tile's first element counted from the run start
+    uint64_t mb;           // tile's first element in the message arrays
     uint64_t run_n;        // elements of the run
     uint32_t lane;
 
@@ -353,6 +358,7 @@ struct GuardedIO {
         return b >= run_n ? 0 : (run_n - b >= (uint64_t)kVec ? kVec : (int)(run_n - b));
     }
     __device__ __forceinline__ uint64_t flat(int row) const { return t0 + (uint64_t)(row * kRow) + lane * kVec; }
+    __device__ __forceinline__ uint64_t msg(int row) const { return mb + (uint64_t)(row * kRow) + lane * kVec; }
 
     __device__ __forceinline__ void ld_f32(const float* p, int n, float (&v)[kVec]) const
     {
@@ -394,7 +400,7 @@ struct GuardedIO {
     template <int FMT> __device__ __forceinline__ void load_message(uint32_t m, int row, float (&dq)[kVec]) const
     {
         const uint8_t* codes = a.codes[m];
-        const uint64_t b = first(row);
+        const uint64_t b = msg(row);
         const int n = valid(row);
         if constexpr (FMT == SDL_FMT_FP32) {
             ld_f32(reinterpret_cast<const float*>(codes) + b, n, dq);
@@ -423,7 +429,7 @@ struct GuardedIO {
     __device__ __forceinline__ void store_message(uint32_t m, int row, const uint32_t (&c)[kVec], uint32_t sb) const
     {
         uint8_t* codes = a.codes[m];
-        const uint64_t b = first(row);
+        const uint64_t b = msg(row);
         const int n = valid(row);
         if constexpr (FMT == SDL_FMT_FP32) {
             float v[kVec];
@@ -587,10 +593,10 @@ void sdl_kernel(const Args a)
     const uint64_t run_n = a.runs[r].numel;
     const uint64_t tile = (uint64_t)(wg - a.runs[r].first_wg) * kGroup;   // first element of the tile in the run
     if (a.runs[r].vec && run_n - tile >= (uint64_t)kGroup) {
-        const TileIO io{a, run_off + tile, tile, threadIdx.x};
+        const TileIO io{a, run_off + tile, a.runs[r].msg + tile, threadIdx.x};
         process<MODE, FMT, MT, ALIASED, EMIT>(a, io);
     } else {
-        const GuardedIO io{a, run_off + tile, tile, run_n, threadIdx.x};
+        const GuardedIO io{a, run_off + tile, tile, a.runs[r].msg + tile, run_n, threadIdx.x};
         process<MODE, FMT, 0, ALIASED, EMIT>(a, io);
     }
 }
@@ -688,10 +694,10 @@ struct RunBuilder {
     uint64_t n_wg = 0;
     explicit RunBuilder(Args* args) : a(args) { a->n_runs = 0; }
     bool full() const { return a->n_runs == kMaxRuns; }
-    void add(uint64_t offset, uint64_t numel, bool vec)
+    void add(uint64_t offset, uint64_t numel, bool vec, uint64_t msg = 0)
     {
         Run& r = a->runs[a->n_runs++];
-        r.offset = offset; r.numel = numel; r.first_wg = (uint32_t)n_wg; r.vec = vec ? 1u : 0u;
+        r.offset = offset; r.numel = numel; r.msg = msg; r.first_wg = (uint32_t)n_wg; r.vec = vec ? 1u : 0u;
         n_wg += (numel + kGroup - 1) / kGroup;
     }
 };
@@ -828,29 +834,125 @@ int sdl_fragment_outer_step(float* g, float* mom, const void* const* w_send, voi
     return run_single_span<kFused>(a, n, fmt, vec, stream);
 }
 
-int sdl_fragment_outer_step_plan(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
-                                 const void* const* w_send_base, void* const* w_now_base, uint32_t M,
-                                 sdl_format_t fmt, float lr, float mu, float alpha, void* stream)
+}  // extern "C"
+
+// One mode over all runs of fragment p, on flat model arrays; the fragment's messages are
+// the concatenation of its runs, each padded to a whole number of 512-element tiles.
+template <int MODE>
+static int launch_fragment(Args& a, const sdl_plan_t* plan, uint32_t p, bool vec, sdl_format_t fmt, void* stream)
 {
     const sdl_span_t* runs = nullptr;
     uint32_t n_runs = 0;
     int rc = sdl_plan_fragment_runs(plan, p, &runs, &n_runs);
     if (rc != SDL_OK) return rc;
-    Args a;
-    bool vec = false;
-    rc = fill_fused_args(a, g_base, mom_base, w_send_base, w_now_base, M, fmt, lr, mu, alpha, &vec);
-    if (rc != SDL_OK) return rc;
+    uint64_t msg = 0;
     for (uint32_t first = 0; first < n_runs; first += kMaxRuns) {
         RunBuilder rb(&a);
         for (uint32_t i = first; i < n_runs && i < first + kMaxRuns; ++i) {
             // a run keeps the 16-byte alignment of the bases when it starts on a multiple of 8 elements
-            rb.add(runs[i].offset, runs[i].numel, vec && (runs[i].offset % 8 == 0));
+            rb.add(runs[i].offset, runs[i].numel, vec && (runs[i].offset % 8 == 0), msg);
+            msg += (runs[i].numel + kGroup - 1) / kGroup * kGroup;
         }
         if (rb.n_wg > 0x7fffffffull) return SDL_ERR_UNSUPPORTED;
-        hipError_t e = launch<kFused>(a, fmt, (uint32_t)rb.n_wg, (hipStream_t)stream);
+        hipError_t e = launch<MODE>(a, fmt, (uint32_t)rb.n_wg, (hipStream_t)stream);
         if (e != hipSuccess) return SDL_ERR_DEVICE;
     }
     return SDL_OK;
+}
+
+extern "C" {
+
+int sdl_plan_message_bytes(const sdl_plan_t* plan, uint32_t p, sdl_format_t fmt, size_t* code_bytes,
+                           size_t* scale_bytes)
+{
+    const sdl_span_t* runs = nullptr;
+    uint32_t n_runs = 0;
+    int rc = sdl_plan_fragment_runs(plan, p, &runs, &n_runs);
+    if (rc != SDL_OK) return rc;
+    if (!valid_format(fmt)) return SDL_ERR_INVALID_ARG;
+    uint64_t padded = 0;
+    for (uint32_t i = 0; i < n_runs; ++i) padded += (runs[i].numel + kGroup - 1) / kGroup * kGroup;
+    sdl_exchange_bytes(fmt, padded, code_bytes, scale_bytes);
+    return SDL_OK;
+}
+
+int sdl_fragment_outer_step_plan(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
+                                 const void* const* w_send_base, void* const* w_now_base, uint32_t M,
+                                 sdl_format_t fmt, float lr, float mu, float alpha, void* stream)
+{
+    if (!plan || p >= sdl_plan_num_fragments(plan)) return SDL_ERR_INVALID_ARG;
+    Args a;
+    bool vec = false;
+    int rc = fill_fused_args(a, g_base, mom_base, w_send_base, w_now_base, M, fmt, lr, mu, alpha, &vec);
+    if (rc != SDL_OK) return rc;
+    return launch_fragment<kFused>(a, plan, p, vec, fmt, stream);
+}
+
+int sdl_quantize_outer_grad_plan(const sdl_plan_t* plan, uint32_t p, const float* g_base,
+                                 const void* const* w_send_base, uint32_t M, sdl_format_t fmt,
+                                 void* const* codes, void* const* scales, void* stream)
+{
+    if (!plan || p >= sdl_plan_num_fragments(plan)) return SDL_ERR_INVALID_ARG;
+    if (!valid_format(fmt) || M == 0 || M > SDL_MAX_WORKERS) return SDL_ERR_INVALID_ARG;
+    const bool scaled = fmt == SDL_FMT_E4M3 || fmt == SDL_FMT_E3M0;
+    if (!g_base || !w_send_base || !codes || (scaled && !scales)) return SDL_ERR_INVALID_ARG;
+    if (!aligned(g_base, 4)) return SDL_ERR_ALIGNMENT;
+    Args a;
+    std::memset(&a, 0, sizeof(a));
+    a.g = const_cast<float*>(g_base);
+    a.M = M;
+    bool vec = aligned(g_base, 16);
+    for (uint32_t m = 0; m < M; ++m) {
+        if (!w_send_base[m] || !codes[m] || (scaled && !scales[m])) return SDL_ERR_INVALID_ARG;
+        if (!aligned(w_send_base[m], 2) || !aligned(codes[m], code_align(fmt))) return SDL_ERR_ALIGNMENT;
+        vec = vec && aligned(w_send_base[m], 16) && aligned(codes[m], 16);
+        a.w_send[m] = static_cast<const uint16_t*>(w_send_base[m]);
+        a.codes[m] = static_cast<uint8_t*>(codes[m]);
+        a.scales[m] = scaled ? static_cast<uint8_t*>(scales[m]) : nullptr;
+    }
+    return launch_fragment<kQuantize>(a, plan, p, vec, fmt, stream);
+}
+
+int sdl_dequant_reduce_nesterov_plan(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
+                                     const void* const* codes, const void* const* scales, uint32_t M,
+                                     sdl_format_t fmt, float lr, float mu, void* stream)
+{
+    if (!plan || p >= sdl_plan_num_fragments(plan)) return SDL_ERR_INVALID_ARG;
+    if (!valid_format(fmt) || M == 0 || M > SDL_MAX_WORKERS) return SDL_ERR_INVALID_ARG;
+    const bool scaled = fmt == SDL_FMT_E4M3 || fmt == SDL_FMT_E3M0;
+    if (!g_base || !mom_base || !codes || (scaled && !scales)) return SDL_ERR_INVALID_ARG;
+    if (!aligned(g_base, 4) || !aligned(mom_base, 4)) return SDL_ERR_ALIGNMENT;
+    Args a;
+    std::memset(&a, 0, sizeof(a));
+    a.g = g_base; a.mom = mom_base; a.M = M; a.lr = lr; a.mu = mu;
+    bool vec = aligned(g_base, 16) && aligned(mom_base, 16);
+    for (uint32_t m = 0; m < M; ++m) {
+        if (!codes[m] || (scaled && !scales[m])) return SDL_ERR_INVALID_ARG;
+        if (!aligned(codes[m], code_align(fmt))) return SDL_ERR_ALIGNMENT;
+        vec = vec && aligned(codes[m], 16);
+        a.codes[m] = static_cast<uint8_t*>(const_cast<void*>(codes[m]));
+        a.scales[m] = scaled ? static_cast<uint8_t*>(const_cast<void*>(scales[m])) : nullptr;
+    }
+    return launch_fragment<kReduce>(a, plan, p, vec, fmt, stream);
+}
+
+int sdl_merge_overlap_plan(const sdl_plan_t* plan, uint32_t p, const float* g_new_base, void* const* w_now_base,
+                           uint32_t M, float alpha, void* stream)
+{
+    if (!plan || p >= sdl_plan_num_fragments(plan)) return SDL_ERR_INVALID_ARG;
+    if (M == 0 || M > SDL_MAX_WORKERS || !g_new_base || !w_now_base) return SDL_ERR_INVALID_ARG;
+    if (!aligned(g_new_base, 4)) return SDL_ERR_ALIGNMENT;
+    Args a;
+    std::memset(&a, 0, sizeof(a));
+    a.g = const_cast<float*>(g_new_base); a.M = M; a.alpha = alpha; a.one_minus_alpha = 1.0f - alpha;
+    bool vec = aligned(g_new_base, 16);
+    for (uint32_t m = 0; m < M; ++m) {
+        if (!w_now_base[m]) return SDL_ERR_INVALID_ARG;
+        if (!aligned(w_now_base[m], 2)) return SDL_ERR_ALIGNMENT;
+        vec = vec && aligned(w_now_base[m], 16);
+        a.w_now[m] = static_cast<uint16_t*>(w_now_base[m]);
+    }
+    return launch_fragment<kMerge>(a, plan, p, vec, SDL_FMT_FP32, stream);
 }
 
 int sdl_copy_bytes(void* dst, const void* src, uint64_t nbytes, void* stream)

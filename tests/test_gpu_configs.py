@@ -144,3 +144,38 @@ def test_config_stress_m8(fmt):
     oracle.dequant_reduce_nesterov(ref.g, ref.mom, rc, rs, f, wl.lr, wl.mu)
     assert_f32_close(host_f32(model.g[sl][lo:lo + width]), ref.g, "stress reduce g")
     assert_f32_close(host_f32(model.mom[sl][lo:lo + width]), ref.mom, "stress reduce mom")
+
+
+def test_plan_call_with_many_ragged_runs():
+    """More runs than one launch holds (16), ragged and partly unaligned: spans whose lengths are
+    not multiples of 32 are never joined, so every span is its own run, with its own block grid."""
+    rng = np.random.default_rng(3)
+    numel = [int(x) for x in rng.integers(1, 5000, 45)] + [4096, 512, 33, 2048 * 3]
+    block = [i % 7 for i in range(len(numel))]
+    P, M, fmt = 3, 3, sdl.FMT_E3M0
+    plan = sdl.sdl_fragment_plan(numel, block, 7, P, sdl.PATTERN_STRIDED, 100, 1)
+    total = plan.total_numel
+    g, mom, w_send, w_now = workloads.make_span(total, M, tau=1, delta="student_t3", device=DEV)
+    host = HostCopy(g, mom, w_send, w_now)
+    for p in range(P):
+        runs = sdl.sdl_plan_fragment_runs(plan, p)
+        assert len(runs) > 16 or p > 0
+        sdl.sdl_fragment_outer_step_plan(plan, p, g, mom, w_send, w_now, fmt, 0.7, 0.9, 0.5)
+        for off, n, _ in sdl.sdl_plan_fragment_spans(plan, p):
+            sl = slice(off, off + n)
+            oracle.fragment_outer_step(host.g[sl], host.mom[sl], [w[sl] for w in host.w_send],
+                                       [w[sl] for w in host.w_now], fmt, 0.7, 0.9, 0.5)
+    torch.cuda.synchronize()
+    assert_f32_close(host_f32(g), host.g, "ragged plan g")
+    assert_f32_close(host_f32(mom), host.mom, "ragged plan mom")
+    for m in range(M):
+        assert_bf16_within_ulp(host_bits(w_now[m]), host.w_now[m], f"ragged plan w_now[{m}]")
+
+
+@pytest.mark.parametrize("M", [6, 16])
+def test_generic_replica_count_large_span(M):
+    """Replica counts without a compile-time variant, on a span of several thousand tiles."""
+    n = 3_000_000 + 77
+    g, mom, w_send, w_now = workloads.make_span(n, M, tau=1, delta="outliers", device=DEV)
+    check_fused_against_oracle(g, mom, w_send, w_now, sdl.FMT_E3M0, 0.7, 0.9, 0.5, emit=False,
+                               what=f"generic M={M}")

@@ -1,0 +1,102 @@
+"""Algorithm 2 end to end on the GPU: the schedule driver walks T inner steps of a small
+synthetic model (inner updates are seeded noise, identical on both sides) and must leave the
+global parameters, the momentum and every replica where the oracle's walk leaves them."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2501_18512_amd as sdl
+import workloads
+from gpu_util import assert_bf16_within_ulp, assert_f32_close, host_bits, host_f32
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _small_model(seed=0):
+    """7 blocks of 4 parameter groups with assorted (also ragged) sizes + embedding + head."""
+    rng = np.random.default_rng(seed)
+    numel, block = [4096], [sdl.UNIT_PRE]
+    for b in range(7):
+        for k in range(4):
+            numel.append(int(rng.choice([512, 1024, 2048 + 32, 640, 100, 33, 4096])))
+            block.append(b)
+    numel += [64, 4096]
+    block += [sdl.UNIT_POST, sdl.UNIT_POST]
+    return numel, block, 7
+
+
+@pytest.mark.parametrize("taus,P,pattern,fmt", [
+    ((0, 0), 3, sdl.PATTERN_STRIDED, sdl.FMT_E3M0),        # no overlap: fused at the send step
+    ((1, 1), 3, sdl.PATTERN_STRIDED, sdl.FMT_E3M0),        # the paper's main setting
+    ((5, 5, 5, 5), 4, sdl.PATTERN_STRIDED, sdl.FMT_E3M0),  # tau larger than the spacing of fragments
+    ((1, 4), 2, sdl.PATTERN_SEQUENTIAL, sdl.FMT_E4M3),     # slack between workers
+    ((0, 3, 2), 7, sdl.PATTERN_STRIDED, sdl.FMT_BF16),
+    ((2, 2), 1, sdl.PATTERN_STRIDED, sdl.FMT_FP32),        # P = 1: DiLoCo with overlap
+])
+def test_engine_matches_oracle_walk(taus, P, pattern, fmt):
+    H, T, M = 12, 3 * 12 + 9, len(taus)
+    lr, mu, alpha = 0.7, 0.9, 0.5
+    numel, block, L = _small_model()
+    plan = sdl.sdl_fragment_plan(numel, block, L, P, pattern, H, min(taus))
+    ref_plan = oracle.fragment_plan(numel, block, L, P, pattern, H, min(taus))
+    total = plan.total_numel
+    g, mom, w, _ = workloads.make_span(total, M, tau=0, delta="normal", device=DEV)
+    ref = oracle.RefEngine(ref_plan, taus, fmt, lr, mu, alpha, host_f32(g), host_f32(mom), [host_bits(x) for x in w])
+    eng = sdl.sdl_engine_create(plan, H, taus, fmt, lr, mu, alpha)
+    codes, scales = [], []
+    for p in range(P):
+        cb, sb = sdl.sdl_plan_message_bytes(plan, p, fmt)
+        for m in range(M):
+            codes.append(torch.zeros(max(cb, 16), dtype=torch.uint8, device=DEV))
+            scales.append(torch.zeros(max(sb, 16), dtype=torch.uint8, device=DEV))
+    sdl.sdl_engine_bind(eng, g, mom, w, codes, scales)
+    gen = torch.Generator(DEV).manual_seed(7)
+    events = 0
+    for t in range(1, T + 1):
+        # inner step: the same seeded noise moves every replica on both sides
+        for m in range(M):
+            noise = torch.randn(total, device=DEV, generator=gen) * 3e-4
+            w[m].copy_((w[m].float() + noise).bfloat16())
+            hn = torch.from_numpy(ref.w[m].view(np.int16)).view(torch.bfloat16).float() + noise.cpu()
+            ref.w[m][:] = host_bits(hn.bfloat16())
+        got = sdl.sdl_engine_step(eng, t)
+        want = ref.step(t)
+        assert got == want, (t, got, want)
+        assert got[0] == len(sdl.sdl_plan_events(plan, t)[0])
+        events += got[0]
+    torch.cuda.synchronize()
+    assert events >= 2 * P
+    assert_f32_close(host_f32(g), ref.g, "engine g")
+    assert_f32_close(host_f32(mom), ref.mom, "engine mom")
+    for m in range(M):
+        assert_bf16_within_ulp(host_bits(w[m]), ref.w[m], f"engine w[{m}]")
+    assert float(np.abs(ref.mom).max()) > 0
+
+
+def test_fragment_level_calls_match_span_level_calls():
+    """quantize / reduce / merge on a whole fragment = the same calls span by span."""
+    numel, block, L = _small_model(seed=1)
+    P, M, fmt = 2, 2, sdl.FMT_E3M0
+    plan = sdl.sdl_fragment_plan(numel, block, L, P, sdl.PATTERN_STRIDED, 10, 1)
+    total = plan.total_numel
+    g, mom, w_send, w_now = workloads.make_span(total, M, tau=1, device=DEV)
+    g2, mom2, wn2 = g.clone(), mom.clone(), [x.clone() for x in w_now]
+    for p in range(P):
+        cb, sb = sdl.sdl_plan_message_bytes(plan, p, fmt)
+        codes = [torch.zeros(cb, dtype=torch.uint8, device=DEV) for _ in range(M)]
+        scales = [torch.zeros(sb, dtype=torch.uint8, device=DEV) for _ in range(M)]
+        sdl.sdl_quantize_outer_grad_plan(plan, p, g, w_send, fmt, codes, scales)
+        sdl.sdl_dequant_reduce_nesterov_plan(plan, p, g, mom, codes, scales, fmt, 0.7, 0.9)
+        sdl.sdl_merge_overlap_plan(plan, p, g, w_now, 0.5)
+        for off, n, _ in sdl.sdl_plan_fragment_spans(plan, p):
+            sl = slice(off, off + n)
+            c, s = sdl.alloc_exchange(fmt, n, M)
+            sdl.sdl_quantize_outer_grad(g2[sl], [x[sl] for x in w_send], n, fmt, c, s)
+            sdl.sdl_dequant_reduce_nesterov(g2[sl], mom2[sl], c, s, n, fmt, 0.7, 0.9)
+            sdl.sdl_merge_overlap(g2[sl], [x[sl] for x in wn2], n, 0.5)
+    torch.cuda.synchronize()
+    assert torch.equal(g, g2) and torch.equal(mom, mom2)
+    for a, b in zip(w_now, wn2):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))

@@ -125,3 +125,21 @@ def test_device_calls_reject_bad_arguments_before_launch():
     sdl.sdl_quantize_outer_grad(0, [0], 0, sdl.FMT_E3M0, [0], [0], stream=0)
     sdl.sdl_fragment_outer_step(0, 0, [0], [0], 0, sdl.FMT_E3M0, 0.7, 0.9, 0.5, stream=0)
     sdl.sdl_merge_overlap(0, [0], 0, 0.5, stream=0)
+
+
+def test_engine_rejects_bad_arguments():
+    plan = sdl.sdl_fragment_plan([64] * 6, list(range(6)), 6, 3, sdl.PATTERN_STRIDED, 10, 1)
+    with pytest.raises(sdl.SdlError):
+        sdl.sdl_engine_create(plan, 10, [10, 1], sdl.FMT_E3M0, 0.7, 0.9, 0.5)      # delay >= H
+    with pytest.raises(sdl.SdlError):
+        sdl.sdl_engine_create(plan, 10, [], sdl.FMT_E3M0, 0.7, 0.9, 0.5)           # M = 0
+    with pytest.raises(sdl.SdlError):
+        sdl.sdl_engine_create(plan, 0, [1], sdl.FMT_E3M0, 0.7, 0.9, 0.5)           # H = 0
+    with pytest.raises(sdl.SdlError):
+        sdl.sdl_engine_create(plan, 5, [1], sdl.FMT_E3M0, 0.7, 0.9, 0.5)           # offsets 0,3,6 need H > 6
+    eng = sdl.sdl_engine_create(plan, 10, [1, 2], sdl.FMT_E3M0, 0.7, 0.9, 0.5)
+    with pytest.raises(sdl.SdlError):
+        sdl.sdl_engine_step(eng, 1, stream=0)                                        # not bound
+    with pytest.raises(sdl.SdlError):
+        sdl.sdl_engine_bind(eng, 0x1000, 0x1000, [0x1000, 0x1000], None, None)      # overlap needs message buffers
+    assert sdl.sdl_plan_message_bytes(plan, 0, sdl.FMT_E3M0) == (2 * 512 // 2, 2 * 512 // 32)
