@@ -111,6 +111,16 @@ typedef struct sdl_plan sdl_plan_t;   /* opaque, host memory, immutable after cr
 int sdl_fragment_plan(const uint64_t* unit_numel, const int32_t* unit_block, uint32_t n_units,
                       uint32_t n_blocks, uint32_t P, sdl_pattern_t pattern, uint32_t H, uint32_t tau,
                       const uint32_t* t_p, sdl_plan_t** out);
+/* The same with options.  SDL_PLAN_PRE_OWN_FRAGMENT: the SDL_UNIT_PRE groups (the embedding)
+ * form fragment 0 by themselves and the blocks are partitioned into fragments 1..P, so the
+ * plan has P + 1 fragments (t_p, if given, has P + 1 entries; the default is
+ * floor(p*H/(P+1))).  This is the layout the appendix's fragment counts imply (three layers
+ * per fragment give 8 / 16 / 36 block fragments and a synchronisation every 11 / 5 / 2 steps,
+ * i.e. H / (fragments + 1)). */
+#define SDL_PLAN_PRE_OWN_FRAGMENT 1u
+int sdl_fragment_plan_ex(const uint64_t* unit_numel, const int32_t* unit_block, uint32_t n_units,
+                         uint32_t n_blocks, uint32_t P, sdl_pattern_t pattern, uint32_t H, uint32_t tau,
+                         const uint32_t* t_p, uint32_t flags, sdl_plan_t** out);
 void sdl_plan_destroy(sdl_plan_t* plan);
 
 uint32_t sdl_plan_num_fragments(const sdl_plan_t* plan);

@@ -60,24 +60,30 @@ class RefPlan:
 
 
 def fragment_plan(unit_numel: Sequence[int], unit_block: Sequence[int], n_blocks: int, P: int,
-                  pattern: int, H: int, tau: int, t_p: Optional[Sequence[int]] = None) -> RefPlan:
+                  pattern: int, H: int, tau: int, t_p: Optional[Sequence[int]] = None,
+                  pre_own_fragment: bool = False) -> RefPlan:
+    """pre_own_fragment: the embedding (UNIT_PRE) is a fragment of its own, number 0, and the
+    blocks use fragments 1..P -- the reading under which the appendix's "8, 16, 36 fragments,
+    one synchronised every 11, 5, 2 steps" adds up (H / (fragments + 1))."""
     assert 1 <= P <= n_blocks and H >= 1 and 0 <= tau < H
+    shift = 1 if pre_own_fragment else 0
     block_fragment = []
     for i in range(n_blocks):
         if pattern == PATTERN_STRIDED:
-            block_fragment.append(i % P)
+            block_fragment.append(shift + i % P)
         else:
             owner = None
             for p in range(P):
                 if (p * n_blocks) // P <= i < ((p + 1) * n_blocks) // P:
                     owner = p
-            block_fragment.append(owner)
+            block_fragment.append(shift + owner)
+    P = P + shift
     offsets = [(p * H) // P for p in range(P)] if t_p is None else [int(x) for x in t_p]
     spans = [[] for _ in range(P)]
     pos = 0
     for u, (numel, blk) in enumerate(zip(unit_numel, unit_block)):
         if blk == UNIT_PRE:
-            p = block_fragment[0]
+            p = 0 if pre_own_fragment else block_fragment[0]
         elif blk == UNIT_POST:
             p = block_fragment[n_blocks - 1]
         else:

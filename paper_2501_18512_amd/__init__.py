@@ -45,6 +45,8 @@ def _load() -> ctypes.CDLL:
     pp = ctypes.POINTER(ctypes.c_void_p)
     lib.sdl_fragment_plan.argtypes = [ctypes.POINTER(u64), ctypes.POINTER(ctypes.c_int32), u32, u32, u32,
                                       ctypes.c_int, u32, u32, ctypes.POINTER(u32), ctypes.POINTER(vp)]
+    lib.sdl_fragment_plan_ex.argtypes = [ctypes.POINTER(u64), ctypes.POINTER(ctypes.c_int32), u32, u32, u32,
+                                         ctypes.c_int, u32, u32, ctypes.POINTER(u32), u32, ctypes.POINTER(vp)]
     lib.sdl_plan_destroy.argtypes = [vp]
     lib.sdl_plan_destroy.restype = None
     lib.sdl_plan_num_fragments.argtypes = [vp]
@@ -144,6 +146,26 @@ class Plan:
     @property
     def total_numel(self) -> int:
         return _lib.sdl_plan_total_numel(self._h)
+
+
+PLAN_PRE_OWN_FRAGMENT = 1
+
+
+def sdl_fragment_plan_ex(unit_numel: Sequence[int], unit_block: Sequence[int], n_blocks: int, P: int,
+                         pattern: int = PATTERN_STRIDED, H: int = 100, tau: int = 0,
+                         t_p: Optional[Sequence[int]] = None, flags: int = 0) -> Plan:
+    n = len(unit_numel)
+    assert len(unit_block) == n
+    numel = (ctypes.c_uint64 * n)(*unit_numel)
+    block = (ctypes.c_int32 * n)(*unit_block)
+    offs = None if t_p is None else (ctypes.c_uint32 * len(t_p))(*t_p)
+    n_frag = P + (1 if flags & PLAN_PRE_OWN_FRAGMENT else 0)
+    if t_p is not None and len(t_p) != n_frag:
+        raise SdlError(-1, "sdl_fragment_plan_ex")
+    out = ctypes.c_void_p()
+    _check(_lib.sdl_fragment_plan_ex(numel, block, n, n_blocks, P, pattern, H, tau, offs, flags,
+                                     ctypes.byref(out)), "sdl_fragment_plan_ex")
+    return Plan(out.value)
 
 
 def sdl_fragment_plan(unit_numel: Sequence[int], unit_block: Sequence[int], n_blocks: int, P: int,

@@ -56,7 +56,18 @@ int sdl_fragment_plan(const uint64_t* unit_numel, const int32_t* unit_block, uin
                       uint32_t n_blocks, uint32_t P, sdl_pattern_t pattern, uint32_t H, uint32_t tau,
                       const uint32_t* t_p, sdl_plan_t** out)
 {
+    return sdl_fragment_plan_ex(unit_numel, unit_block, n_units, n_blocks, P, pattern, H, tau, t_p, 0u, out);
+}
+
+int sdl_fragment_plan_ex(const uint64_t* unit_numel, const int32_t* unit_block, uint32_t n_units,
+                         uint32_t n_blocks, uint32_t P, sdl_pattern_t pattern, uint32_t H, uint32_t tau,
+                         const uint32_t* t_p, uint32_t flags, sdl_plan_t** out)
+{
     if (!out || (n_units && (!unit_numel || !unit_block))) return SDL_ERR_INVALID_ARG;
+    if (flags & ~(uint32_t)SDL_PLAN_PRE_OWN_FRAGMENT) return SDL_ERR_INVALID_ARG;
+    // with the flag, fragment 0 holds the SDL_UNIT_PRE groups alone and the blocks use 1..P
+    const uint32_t shift = (flags & SDL_PLAN_PRE_OWN_FRAGMENT) ? 1u : 0u;
+    const uint32_t n_frag = P + shift;
     if (P == 0 || n_blocks == 0 || P > n_blocks || H == 0 || tau >= H) return SDL_ERR_INVALID_ARG;
     if (pattern != SDL_PATTERN_STRIDED && pattern != SDL_PATTERN_SEQUENTIAL) return SDL_ERR_INVALID_ARG;
     for (uint32_t u = 0; u < n_units; ++u) {
@@ -65,32 +76,35 @@ int sdl_fragment_plan(const uint64_t* unit_numel, const int32_t* unit_block, uin
             return SDL_ERR_INVALID_ARG;
     }
     if (t_p)
-        for (uint32_t p = 0; p < P; ++p)
+        for (uint32_t p = 0; p < n_frag; ++p)
             if (t_p[p] >= H) return SDL_ERR_INVALID_ARG;
 
     sdl_plan* plan = nullptr;
     try {
         plan = new sdl_plan();
-        plan->P = P; plan->H = H; plan->tau = tau; plan->n_blocks = n_blocks;
-        plan->offset.resize(P);
-        for (uint32_t p = 0; p < P; ++p)
-            plan->offset[p] = t_p ? t_p[p] : (uint32_t)(((uint64_t)p * H) / P);
+        plan->P = n_frag; plan->H = H; plan->tau = tau; plan->n_blocks = n_blocks;
+        plan->offset.resize(n_frag);
+        for (uint32_t p = 0; p < n_frag; ++p)
+            plan->offset[p] = t_p ? t_p[p] : (uint32_t)(((uint64_t)p * H) / n_frag);
         plan->block_owner.resize(n_blocks);
         for (uint32_t i = 0; i < n_blocks; ++i)
-            plan->block_owner[i] = owner_of_block(i, n_blocks, P, pattern);
-        plan->spans.resize(P);
+            plan->block_owner[i] = shift + owner_of_block(i, n_blocks, P, pattern);
+        plan->spans.resize(n_frag);
         uint64_t pos = 0;
         for (uint32_t u = 0; u < n_units; ++u) {
             int32_t b = unit_block[u];
-            uint32_t blk = (b == SDL_UNIT_PRE) ? 0u : (b == SDL_UNIT_POST) ? n_blocks - 1 : (uint32_t)b;
+            uint32_t owner;
+            if (b == SDL_UNIT_PRE) owner = shift ? 0u : plan->block_owner[0];
+            else if (b == SDL_UNIT_POST) owner = plan->block_owner[n_blocks - 1];
+            else owner = plan->block_owner[(uint32_t)b];
             sdl_span_t s;
             s.offset = pos; s.numel = unit_numel[u]; s.unit = (int32_t)u;
-            plan->spans[plan->block_owner[blk]].push_back(s);
+            plan->spans[owner].push_back(s);
             pos += unit_numel[u];
         }
         plan->total = pos;
-        plan->runs.resize(P);
-        for (uint32_t p = 0; p < P; ++p) plan->runs[p] = join_spans(plan->spans[p]);
+        plan->runs.resize(n_frag);
+        for (uint32_t p = 0; p < n_frag; ++p) plan->runs[p] = join_spans(plan->spans[p]);
     } catch (const std::bad_alloc&) {
         delete plan;
         return SDL_ERR_NOMEM;

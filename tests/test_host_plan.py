@@ -65,6 +65,27 @@ def test_plan_matches_oracle(shape, P, pattern, H, tau, t_p):
         assert sdl.sdl_plan_events(plan, t) == (ref.sends(t), ref.receives(t))
 
 
+@pytest.mark.parametrize("shape,P,pattern,H", [("100m", 4, sdl.PATTERN_STRIDED, 100), ("1b", 8, sdl.PATTERN_STRIDED, 100),
+                                               ("100m", 3, sdl.PATTERN_SEQUENTIAL, 50)])
+def test_plan_with_embedding_fragment_matches_oracle(shape, P, pattern, H):
+    numel, block, _ = workloads.SHAPES[shape].units()
+    L = workloads.SHAPES[shape].n_layers
+    ref = oracle.fragment_plan(numel, block, L, P, pattern, H, 1, pre_own_fragment=True)
+    plan = sdl.sdl_fragment_plan_ex(numel, block, L, P, pattern, H, 1, flags=sdl.PLAN_PRE_OWN_FRAGMENT)
+    assert plan.num_fragments == P + 1 == ref.P
+    assert [sdl.sdl_plan_block_fragment(plan, i) for i in range(L)] == ref.block_fragment
+    for p in range(P + 1):
+        assert sdl.sdl_plan_offset(plan, p) == ref.offsets[p]
+        assert sdl.sdl_plan_fragment_spans(plan, p) == ref.spans[p]
+    assert sdl.sdl_plan_fragment_spans(plan, 0) == [(0, numel[0], 0)]
+    for t in range(1, 2 * H + 3):
+        assert sdl.sdl_plan_events(plan, t) == (ref.sends(t), ref.receives(t))
+    with pytest.raises(sdl.SdlError):
+        sdl.sdl_fragment_plan_ex(numel, block, L, P, pattern, H, 1, flags=2)
+    with pytest.raises(sdl.SdlError):
+        sdl.sdl_fragment_plan_ex(numel, block, L, P, pattern, H, 1, t_p=[0] * P, flags=sdl.PLAN_PRE_OWN_FRAGMENT)
+
+
 def test_runs_respect_ragged_spans():
     # adjacent spans are joined only while the run so far is a whole number of scale blocks
     plan = sdl.sdl_fragment_plan([40, 24, 64, 32], [0, 0, 0, 0], 1, 1)

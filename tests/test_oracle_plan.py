@@ -93,3 +93,22 @@ def test_colliding_offsets_all_reported():
     assert plan.sends(100) == [0, 1]
     assert plan.sends(130) == [2] and plan.receives(130) == [0, 1]
     assert plan.receives(160) == [2] and plan.sends(160) == [3]
+
+
+def test_embedding_as_its_own_fragment_reproduces_the_appendix_counts():
+    """Appendix (compute utilisation): 3 layers per fragment -> 8 / 16 / 36 fragments for 24 / 48 /
+    108 layers, and some fragment is synchronised every 11 / 5 / 2 steps with H = 100.  The step
+    counts only add up with one more fragment (the embedding): floor(100 / (fragments + 1))."""
+    for L, per, P, every in _rows("fragment_counts.txt"):
+        L, per, P, every = int(L), int(per), int(P), int(every)
+        numel = [1000] + [10] * L + [5, 1000]
+        block = [-1] + list(range(L)) + [-2, -2]
+        assert 100 // (P + 1) == every
+        offs = [p * every for p in range(P + 1)]
+        plan = fragment_plan(numel, block, L, P, PATTERN_STRIDED, 100, 1, t_p=offs, pre_own_fragment=True)
+        assert plan.P == P + 1
+        assert plan.spans[0] == [(0, 1000, 0)]                              # the embedding alone
+        assert all(len([b for b in plan.block_fragment if b == p]) == per for p in range(1, P + 1))
+        syncs = sorted(t for t in range(100, 200) for _ in plan.sends(t))     # one period
+        gaps = [b - a for a, b in zip(syncs, syncs[1:])]
+        assert len(syncs) == P + 1 and set(gaps) == {every}
