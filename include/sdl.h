@@ -49,7 +49,8 @@ extern "C" {
 #endif
 
 #define SDL_MAX_WORKERS 16
-#define SDL_BLOCK 32           /* elements per scale byte */
+#define SDL_BLOCK 32           /* elements per scale byte (default formats) */
+#define SDL_MAX_BLOCK 128      /* largest block of the block-scaled formats */
 #define SDL_UNIT_PRE  (-1)     /* parameter group before the first block (embedding) */
 #define SDL_UNIT_POST (-2)     /* parameter group after the last block (final norm, head) */
 
@@ -76,8 +77,18 @@ typedef enum {
  * as sb = max(0, biased_exponent(a) - emax) with emax = 4 (E3M0) or 8 (E4M3), 0 if
  * a is zero or subnormal.  Elements are rounded to the nearest representable
  * magnitude of |x| / 2^(sb-127) in the linear domain, ties to the even code,
- * saturating at the largest magnitude. */
-typedef enum { SDL_FMT_FP32 = 0, SDL_FMT_BF16 = 1, SDL_FMT_E4M3 = 2, SDL_FMT_E3M0 = 3 } sdl_format_t;
+ * saturating at the largest magnitude.
+ *
+ * E3M0 with another scale granularity (the element codes and their packing are the same):
+ *   SDL_FMT_E3M0_B64 / _B128   one scale byte per 64 / 128 elements
+ *   SDL_FMT_E3M0_SPAN          one scale for the whole span (per tensor): exactly the 4 bits
+ *                              per parameter of the paper's accounting of exchanged data.  The
+ *                              scale array of a span is one 4-byte word (4-byte aligned): the
+ *                              fp32 bit pattern of the span's absolute maximum, from whose
+ *                              exponent field the scale byte follows as above.  It is produced
+ *                              by an extra pass over g and w_send (a grid-wide maximum). */
+typedef enum { SDL_FMT_FP32 = 0, SDL_FMT_BF16 = 1, SDL_FMT_E4M3 = 2, SDL_FMT_E3M0 = 3,
+               SDL_FMT_E3M0_B64 = 4, SDL_FMT_E3M0_B128 = 5, SDL_FMT_E3M0_SPAN = 6 } sdl_format_t;
 
 /* Fragment patterns of Section 2.2: interleaved blocks (default) or consecutive blocks. */
 typedef enum { SDL_PATTERN_STRIDED = 0, SDL_PATTERN_SEQUENTIAL = 1 } sdl_pattern_t;
@@ -133,8 +144,9 @@ int sdl_plan_fragment_spans(const sdl_plan_t* plan, uint32_t p, const sdl_span_t
                             uint32_t* n_spans);
 /* The same elements as maximal contiguous runs: neighbouring spans are joined when
  * that leaves every 32-element scale block where it was (all joined spans but the
- * last have a multiple of 32 elements).  Processing the runs instead of the spans
- * gives identical results with fewer launches. */
+ * last have a multiple of 128 elements).  Processing the runs instead of the spans
+ * gives identical results with fewer launches.  (Joining happens at multiples of 128
+ * elements, the largest scale block, so it is valid for every block-scaled format.) */
 int sdl_plan_fragment_runs(const sdl_plan_t* plan, uint32_t p, const sdl_span_t** runs,
                            uint32_t* n_runs);
 int sdl_plan_offset(const sdl_plan_t* plan, uint32_t p, uint32_t* t_p);
@@ -183,7 +195,8 @@ int sdl_merge_overlap(const float* g_new, void* const* w_now, uint32_t M, uint64
  * w_send[m] (the replica as it was at the send step) is only read and may be the same
  * pointer as w_now[m] for all m.  If codes_or_null is not NULL the messages are also
  * written out exactly as sdl_quantize_outer_grad would (scales_or_null then must be
- * given for E4M3 / E3M0). */
+ * given for the scaled formats).  SDL_FMT_E3M0_SPAN always needs scales_or_null: M device
+ * pointers to one 4-byte scale word each, used as workspace even when no message is written. */
 int sdl_fragment_outer_step(float* g, float* mom, const void* const* w_send, void* const* w_now,
                             uint32_t M, uint64_t n, sdl_format_t fmt, float lr, float mu, float alpha,
                             void* const* codes_or_null, void* const* scales_or_null, void* stream);
@@ -191,7 +204,7 @@ int sdl_fragment_outer_step(float* g, float* mom, const void* const* w_send, voi
 /* Fused outer step of a whole fragment of a plan: every run of fragment p, in one
  * kernel launch per group of up to 16 runs.  The pointers are the bases of the flat model arrays
  * (element 0 of the model); run r is processed at element offset runs[r].offset.
- * Messages are not written. */
+ * Messages are not written.  SDL_FMT_E3M0_SPAN is not supported here (SDL_ERR_UNSUPPORTED). */
 int sdl_fragment_outer_step_plan(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
                                  const void* const* w_send_base, void* const* w_now_base, uint32_t M,
                                  sdl_format_t fmt, float lr, float mu, float alpha, void* stream);
@@ -200,7 +213,9 @@ int sdl_fragment_outer_step_plan(const sdl_plan_t* plan, uint32_t p, float* g_ba
  * of a plan, on the flat model arrays (bases = element 0 of the model).  The messages of a
  * fragment are laid out as the concatenation of its runs, each run padded to a multiple
  * of 512 elements; sdl_plan_message_bytes gives the size of codes[m] / scales[m] for that
- * layout.  Argument meaning, arithmetic and errors as in the span-level calls above. */
+ * layout.  For SDL_FMT_E3M0_SPAN the pieces are the fragment's spans (parameter groups)
+ * instead of the joined runs, and scales[m] holds one 4-byte word per span.  Argument
+ * meaning, arithmetic and errors as in the span-level calls above. */
 int sdl_plan_message_bytes(const sdl_plan_t* plan, uint32_t p, sdl_format_t fmt, size_t* code_bytes,
                            size_t* scale_bytes);
 int sdl_quantize_outer_grad_plan(const sdl_plan_t* plan, uint32_t p, const float* g_base,

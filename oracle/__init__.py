@@ -22,7 +22,9 @@ from .plan import (PATTERN_SEQUENTIAL, PATTERN_STRIDED, UNIT_POST, UNIT_PRE,  # 
                    RefPlan, fragment_plan)
 
 FMT_FP32, FMT_BF16, FMT_E4M3, FMT_E3M0 = 0, 1, 2, 3
+FMT_E3M0_B64, FMT_E3M0_B128, FMT_E3M0_SPAN = 4, 5, 6
 BLOCK = 32
+MAX_BLOCK = 128
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "sdl_ref.c")
@@ -152,11 +154,13 @@ def fragment_outer_step_chunked(g, mom, w_send, w_now, fmt, lr, mu, alpha, threa
     `threads` host threads.  Every element's arithmetic is unchanged (the step is
     independent per 32-element block); only the benchmark's CPU baseline uses this."""
     n = g.size
-    if threads <= 1 or n < BLOCK * threads:
+    # cutting is only valid where no scale is shared across the cut: never for the whole-span
+    # scale, and at multiples of the largest scale block (128) otherwise
+    if threads <= 1 or n < MAX_BLOCK * threads or fmt == FMT_E3M0_SPAN:
         fragment_outer_step(g, mom, w_send, w_now, fmt, lr, mu, alpha)
         return 1
     per = -(-n // threads)
-    per = -(-per // BLOCK) * BLOCK
+    per = -(-per // MAX_BLOCK) * MAX_BLOCK
     ranges = [(lo, min(lo + per, n)) for lo in range(0, n, per)]
     aliased = all(a is b for a, b in zip(w_send, w_now))
 

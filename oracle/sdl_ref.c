@@ -28,7 +28,10 @@
  *   - Scaling: blocks of 32 consecutive elements share one power-of-two scale
  *     byte sb (value 2^(sb-127)), chosen from the block's absolute maximum a
  *     so that a / scale lies in [16, 32) for E3M0 (largest element magnitude
- *     exponent 4) and in [256, 512) for E4M3 (largest exponent 8).
+ *     exponent 4) and in [256, 512) for E4M3 (largest exponent 8).  Variants of
+ *     E3M0 use blocks of 64 or 128 elements, or the whole span (one scale per
+ *     tensor, the 4.0 bits per parameter that the paper's table of exchanged
+ *     data implies).
  *   - Rounding: nearest representable magnitude measured in the linear
  *     domain, ties to the even code, saturating at the largest magnitude.
  *   - Nibble order: element 2j in the low nibble of byte j, 2j+1 in the high.
@@ -49,10 +52,28 @@
 #include <stdlib.h>
 #include <string.h>
 
-/* Exchange formats.  Numbering is this file's own. */
-enum { REF_FMT_FP32 = 0, REF_FMT_BF16 = 1, REF_FMT_E4M3 = 2, REF_FMT_E3M0 = 3 };
+/* Exchange formats.  Numbering is this file's own.  The three last ones are E3M0 with
+ * another scale granularity: blocks of 64 or 128 elements, or one scale for the whole span
+ * (per tensor), which is what the paper's accounting of exactly 4 bits per parameter
+ * suggests.  A whole-span scale is stored as a 4-byte word: the fp32 bit pattern of the
+ * span's absolute maximum (the scale byte follows from its exponent field as for blocks). */
+enum { REF_FMT_FP32 = 0, REF_FMT_BF16 = 1, REF_FMT_E4M3 = 2, REF_FMT_E3M0 = 3,
+       REF_FMT_E3M0_B64 = 4, REF_FMT_E3M0_B128 = 5, REF_FMT_E3M0_SPAN = 6, REF_FMT_COUNT = 7 };
 
-#define REF_BLOCK 32u /* elements that share one scale byte */
+#define REF_BLOCK 32u /* elements that share one scale byte in the default formats */
+
+static int is_e3m0(int fmt) { return fmt == REF_FMT_E3M0 || fmt >= REF_FMT_E3M0_B64; }
+static int is_scaled(int fmt) { return fmt == REF_FMT_E4M3 || is_e3m0(fmt); }
+/* elements per scale; 0 = the whole span */
+static uint64_t block_of(int fmt)
+{
+    switch (fmt) {
+    case REF_FMT_E3M0_B64: return 64;
+    case REF_FMT_E3M0_B128: return 128;
+    case REF_FMT_E3M0_SPAN: return 0;
+    default: return REF_BLOCK;
+    }
+}
 
 /* ---------------------------------------------------------------- helpers */
 
@@ -101,16 +122,16 @@ static unsigned nearest_code(double y, unsigned last, double (*mag)(unsigned))
     return best;
 }
 
-/* Absolute maximum of one block as the biased fp32 exponent field of the
- * largest magnitude; 255 if any element is Inf or NaN. */
-static unsigned block_max_exponent(const float* d, unsigned len)
+/* Absolute maximum of one block: the fp32 bit pattern (sign cleared) of the largest
+ * magnitude, where any Inf / NaN counts as larger than every finite value. */
+static uint32_t block_max_bits(const float* d, uint64_t len)
 {
-    unsigned e_a = 0;
-    for (unsigned i = 0; i < len; ++i) {
-        unsigned e = (f32_bits(d[i]) >> 23) & 0xffu;
-        if (e > e_a) e_a = e;
+    uint32_t a = 0;
+    for (uint64_t i = 0; i < len; ++i) {
+        uint32_t m = f32_bits(d[i]) & 0x7fffffffu;
+        if (m > a) a = m;
     }
-    return e_a;
+    return a;
 }
 
 /* Scale byte for a block whose largest magnitude has biased exponent e_a and
@@ -124,25 +145,30 @@ static unsigned scale_byte(unsigned e_a, unsigned emax)
     return e_a - emax;
 }
 
+/* Element code (sign and magnitude code) of one outer gradient in a block whose largest
+ * magnitude has biased exponent e_a. */
+static unsigned encode_element(float x, unsigned e_a, int fmt)
+{
+    const unsigned emax = is_e3m0(fmt) ? 4u : 8u;
+    const unsigned sign_shift = is_e3m0(fmt) ? 3u : 7u;
+    const unsigned sb = scale_byte(e_a, emax);
+    unsigned s = f32_bits(x) >> 31;
+    unsigned mag_code = 0;
+    if (e_a != 0u && e_a != 255u) {
+        double y = ldexp(fabs((double)x), 127 - (int)sb);
+        mag_code = is_e3m0(fmt) ? nearest_code(y, 7u, e3m0_magnitude) : nearest_code(y, 0x7eu, e4m3_magnitude);
+    }
+    return (s << sign_shift) | mag_code;
+}
+
 /* Encode one block of up to 32 outer gradients into unpacked element codes
  * (one per byte, E3M0 in the low 4 bits / E4M3 in all 8) and its scale byte. */
 static unsigned encode_block(const float* d, unsigned len, int fmt, uint8_t* code)
 {
-    const unsigned emax = (fmt == REF_FMT_E3M0) ? 4u : 8u;
-    const unsigned sign_shift = (fmt == REF_FMT_E3M0) ? 3u : 7u;
-    unsigned e_a = block_max_exponent(d, len);
-    unsigned sb = scale_byte(e_a, emax);
-    for (unsigned i = 0; i < len; ++i) {
-        unsigned s = f32_bits(d[i]) >> 31;
-        unsigned mag_code = 0;
-        if (e_a != 0u && e_a != 255u) {
-            double y = ldexp(fabs((double)d[i]), 127 - (int)sb);
-            mag_code = (fmt == REF_FMT_E3M0) ? nearest_code(y, 7u, e3m0_magnitude)
-                                             : nearest_code(y, 0x7eu, e4m3_magnitude);
-        }
-        code[i] = (uint8_t)((s << sign_shift) | mag_code);
-    }
-    return sb;
+    const unsigned emax = is_e3m0(fmt) ? 4u : 8u;
+    unsigned e_a = block_max_bits(d, len) >> 23;
+    for (unsigned i = 0; i < len; ++i) code[i] = (uint8_t)encode_element(d[i], e_a, fmt);
+    return scale_byte(e_a, emax);
 }
 
 /* Decode one element of a scaled format.  A block whose scale byte is 0xff
@@ -152,7 +178,7 @@ static float decode_scaled(unsigned code, unsigned sb, int fmt)
     if (sb == 0xffu) return bits_f32(0x7fc00000u);
     double mag;
     unsigned s;
-    if (fmt == REF_FMT_E3M0) { mag = e3m0_magnitude(code & 7u); s = (code >> 3) & 1u; }
+    if (is_e3m0(fmt)) { mag = e3m0_magnitude(code & 7u); s = (code >> 3) & 1u; }
     else                     { mag = e4m3_magnitude(code & 0x7fu); s = (code >> 7) & 1u; }
     /* at most 4 significant bits times a power of two no smaller than
      * 2^-136: exactly representable in binary32, subnormals included */
@@ -173,7 +199,9 @@ size_t sdl_ref_exchange_bytes(int fmt, uint64_t n, size_t* code_bytes, size_t* s
     case REF_FMT_FP32: c = (size_t)n * 4; break;
     case REF_FMT_BF16: c = (size_t)n * 2; break;
     case REF_FMT_E4M3: c = (size_t)n; s = ceil_div(n, REF_BLOCK); break;
-    case REF_FMT_E3M0: c = ceil_div(n, 2); s = ceil_div(n, REF_BLOCK); break;
+    case REF_FMT_E3M0: case REF_FMT_E3M0_B64: case REF_FMT_E3M0_B128:
+        c = ceil_div(n, 2); s = ceil_div(n, block_of(fmt)); break;
+    case REF_FMT_E3M0_SPAN: c = ceil_div(n, 2); s = n ? 4 : 0; break;
     default: break;
     }
     if (code_bytes) *code_bytes = c;
@@ -188,7 +216,7 @@ size_t sdl_ref_exchange_bytes(int fmt, uint64_t n, size_t* code_bytes, size_t* s
 int sdl_ref_quantize_outer_grad(const float* g, const uint16_t* const* w_send, uint32_t M,
                                 uint64_t n, int fmt, uint8_t* const* codes, uint8_t* const* scales)
 {
-    if (fmt < 0 || fmt > 3) return -1;
+    if (fmt < 0 || fmt >= REF_FMT_COUNT) return -1;
     for (uint32_t m = 0; m < M; ++m) {
         const uint16_t* w = w_send[m];
         if (fmt == REF_FMT_FP32) {
@@ -201,21 +229,39 @@ int sdl_ref_quantize_outer_grad(const float* g, const uint16_t* const* w_send, u
             for (uint64_t i = 0; i < n; ++i) out[i] = f32_to_bf16_rne(g[i] - bf16_to_f32(w[i]));
             continue;
         }
-        if (fmt == REF_FMT_E3M0) memset(codes[m], 0, ceil_div(n, 2));
-        for (uint64_t b0 = 0; b0 < n; b0 += REF_BLOCK) {
-            unsigned len = (n - b0 < REF_BLOCK) ? (unsigned)(n - b0) : REF_BLOCK;
-            float d[REF_BLOCK];
-            uint8_t c[REF_BLOCK];
-            for (unsigned i = 0; i < len; ++i) d[i] = g[b0 + i] - bf16_to_f32(w[b0 + i]);
-            scales[m][b0 / REF_BLOCK] = (uint8_t)encode_block(d, len, fmt, c);
-            for (unsigned i = 0; i < len; ++i) {
+        if (is_e3m0(fmt)) memset(codes[m], 0, ceil_div(n, 2));
+        const uint64_t block = block_of(fmt) ? block_of(fmt) : (n ? n : 1);
+        const unsigned emax = is_e3m0(fmt) ? 4u : 8u;
+        float* d = (float*)malloc((size_t)(block < n ? block : n) * sizeof(float) + 4);
+        if (!d) return -5;
+        for (uint64_t b0 = 0; b0 < n; b0 += block) {
+            uint64_t len = (n - b0 < block) ? (n - b0) : block;
+            for (uint64_t i = 0; i < len; ++i) d[i] = g[b0 + i] - bf16_to_f32(w[b0 + i]);
+            const uint32_t amax = block_max_bits(d, len);
+            const unsigned e_a = amax >> 23;
+            if (fmt == REF_FMT_E3M0_SPAN) memcpy(scales[m], &amax, 4);
+            else scales[m][b0 / block] = (uint8_t)scale_byte(e_a, emax);
+            for (uint64_t i = 0; i < len; ++i) {
                 uint64_t k = b0 + i;
-                if (fmt == REF_FMT_E4M3) codes[m][k] = c[i];
-                else codes[m][k >> 1] |= (uint8_t)((c[i] & 15u) << ((k & 1u) * 4u));
+                unsigned c = encode_element(d[i], e_a, fmt);
+                if (fmt == REF_FMT_E4M3) codes[m][k] = (uint8_t)c;
+                else codes[m][k >> 1] |= (uint8_t)((c & 15u) << ((k & 1u) * 4u));
             }
         }
+        free(d);
     }
     return 0;
+}
+
+/* Scale byte that governs element i of a scaled message. */
+static unsigned scale_of(const uint8_t* scale, uint64_t i, int fmt)
+{
+    if (fmt == REF_FMT_E3M0_SPAN) {
+        uint32_t amax;
+        memcpy(&amax, scale, 4);
+        return scale_byte(amax >> 23, 4u);
+    }
+    return scale[i / block_of(fmt)];
 }
 
 /* Value that replica m's message holds for element i. */
@@ -224,9 +270,8 @@ static float decode_element(const uint8_t* code, const uint8_t* scale, uint64_t 
     switch (fmt) {
     case REF_FMT_FP32: return ((const float*)code)[i];
     case REF_FMT_BF16: return bf16_to_f32(((const uint16_t*)code)[i]);
-    case REF_FMT_E4M3: return decode_scaled(code[i], scale[i / REF_BLOCK], fmt);
-    default:           return decode_scaled((code[i >> 1] >> ((i & 1u) * 4u)) & 15u,
-                                            scale[i / REF_BLOCK], fmt);
+    case REF_FMT_E4M3: return decode_scaled(code[i], scale_of(scale, i, fmt), fmt);
+    default:           return decode_scaled((code[i >> 1] >> ((i & 1u) * 4u)) & 15u, scale_of(scale, i, fmt), fmt);
     }
 }
 
@@ -237,7 +282,7 @@ int sdl_ref_dequant_reduce_nesterov(float* g, float* mom, const uint8_t* const* 
                                     const uint8_t* const* scales, uint32_t M, uint64_t n, int fmt,
                                     float lr, float mu)
 {
-    if (fmt < 0 || fmt > 3 || M == 0) return -1;
+    if (fmt < 0 || fmt >= REF_FMT_COUNT || M == 0) return -1;
     for (uint64_t i = 0; i < n; ++i) {
         float acc = 0.0f;
         for (uint32_t m = 0; m < M; ++m) {
@@ -284,7 +329,7 @@ int sdl_ref_fragment_outer_step(float* g, float* mom, const uint16_t* const* w_s
                                 float mu, float alpha, uint8_t* const* codes_out,
                                 uint8_t* const* scales_out)
 {
-    if (fmt < 0 || fmt > 3 || M == 0) return -1;
+    if (fmt < 0 || fmt >= REF_FMT_COUNT || M == 0) return -1;
     size_t cb, sb;
     sdl_ref_exchange_bytes(fmt, n, &cb, &sb);
     uint8_t** codes = (uint8_t**)calloc(M, sizeof(uint8_t*));
@@ -319,7 +364,7 @@ int sdl_ref_fragment_outer_step(float* g, float* mom, const uint16_t* const* w_s
  * element code per byte; returns the scale byte. */
 int sdl_ref_encode_block(const float* delta, uint32_t len, int fmt, uint8_t* code_out)
 {
-    if (len == 0 || len > REF_BLOCK || (fmt != REF_FMT_E3M0 && fmt != REF_FMT_E4M3)) return -1;
+    if (len == 0 || len > REF_BLOCK || !is_scaled(fmt)) return -1;
     return (int)encode_block(delta, len, fmt, code_out);
 }
 

@@ -34,7 +34,7 @@ int sdl_engine_create(const sdl_plan_t* plan, uint32_t H, uint32_t M, const uint
                       float lr, float mu, float alpha, sdl_engine_t** out)
 {
     if (!plan || !out || !tau_m || M == 0 || M > SDL_MAX_WORKERS || H == 0) return SDL_ERR_INVALID_ARG;
-    if (fmt < SDL_FMT_FP32 || fmt > SDL_FMT_E3M0) return SDL_ERR_INVALID_ARG;
+    if (fmt < SDL_FMT_FP32 || fmt > SDL_FMT_E3M0_SPAN) return SDL_ERR_INVALID_ARG;
     for (uint32_t m = 0; m < M; ++m)
         if (tau_m[m] >= H) return SDL_ERR_INVALID_ARG;
     sdl_engine* e = nullptr;
@@ -73,8 +73,10 @@ int sdl_engine_bind(sdl_engine_t* e, float* g_base, float* mom_base, void* const
                     void* const* scales)
 {
     if (!e || !g_base || !mom_base || !w_base) return SDL_ERR_INVALID_ARG;
-    const bool need_messages = e->delay_max > 0;
-    const bool scaled = e->fmt == SDL_FMT_E4M3 || e->fmt == SDL_FMT_E3M0;
+    // without any delay the fused call is used, which keeps the messages in registers; the
+    // whole-span scale has no fused fragment call, so it always goes through messages
+    const bool need_messages = e->delay_max > 0 || e->fmt == SDL_FMT_E3M0_SPAN;
+    const bool scaled = e->fmt >= SDL_FMT_E4M3;
     if (need_messages && (!codes || (scaled && !scales))) return SDL_ERR_INVALID_ARG;
     for (uint32_t m = 0; m < e->M; ++m)
         if (!w_base[m]) return SDL_ERR_INVALID_ARG;
@@ -103,7 +105,7 @@ int sdl_engine_step(sdl_engine_t* e, uint64_t t, void* stream, uint32_t* n_sent,
         const uint64_t s0 = e->offset[p];
         if (t > s0 && (t - s0) % e->H == 0) {
             if (e->sent_at[p] != 0) return SDL_ERR_INVALID_ARG;      // previous message not consumed: steps skipped
-            if (e->delay_max == 0) {
+            if (e->delay_max == 0 && e->fmt != SDL_FMT_E3M0_SPAN) {
                 // no overlap anywhere: the whole outer step at once
                 int rc = sdl_fragment_outer_step_plan(e->plan, p, e->g, e->mom, e->w.data(), e->w.data(), M, e->fmt,
                                                       e->lr, e->mu, e->alpha, stream);

@@ -35,10 +35,18 @@ constexpr int kRows = 2;                      // rows of a tile
 constexpr int kWave = 64;                     // lanes per workgroup: one wavefront
 constexpr int kRow = kVec * kWave;            // parameters per row (256)
 constexpr int kGroup = kRow * kRows;          // parameters per workgroup tile (512)
-constexpr int kBlockLanes = SDL_BLOCK / kVec; // lanes that share a scale block (8)
 constexpr int kMaxRuns = 16;                  // runs per launch
 
-enum Mode { kQuantize = 0, kReduce = 1, kMerge = 2, kFused = 3 };
+enum Mode { kQuantize = 0, kReduce = 1, kMerge = 2, kFused = 3, kAbsmax = 4 };
+
+constexpr bool is_e3m0(int f) { return f == SDL_FMT_E3M0 || f >= SDL_FMT_E3M0_B64; }
+constexpr bool is_scaled(int f) { return f == SDL_FMT_E4M3 || is_e3m0(f); }
+constexpr bool is_span_scaled(int f) { return f == SDL_FMT_E3M0_SPAN; }
+// elements that share a scale (0: the whole span)
+constexpr int block_elems(int f)
+{
+    return f == SDL_FMT_E3M0_B64 ? 64 : f == SDL_FMT_E3M0_B128 ? 128 : f == SDL_FMT_E3M0_SPAN ? 0 : SDL_BLOCK;
+}
 
 struct Run {
     uint64_t offset;     // first element of the run in the flat arrays
@@ -46,6 +54,8 @@ struct Run {
     uint64_t msg;        // where the run starts in the message arrays, in elements (a multiple of 512)
     uint32_t first_wg;   // first workgroup of the launch that works on this run
     uint32_t vec;        // 1: every array of this run is 16-byte aligned at its start
+    uint32_t sidx;       // whole-span scale: index of the run's 4-byte scale word
+    uint32_t pad_;
 };
 
 struct Args {
@@ -107,15 +117,29 @@ __device__ __forceinline__ void unpack_bf16(const uint32_t (&u)[2], float (&v)[k
     v[0] = bf16_lo(u[0]); v[1] = bf16_hi(u[0]); v[2] = bf16_lo(u[1]); v[3] = bf16_hi(u[1]);
 }
 
-// Maximum over the eight lanes that share a scale block: lanes 8k .. 8k+7.
-__device__ __forceinline__ uint32_t block_max(uint32_t v)
+// Maximum over the LANES consecutive lanes that share a scale block (8, 16, 32 or all 64).
+template <int LANES>
+__device__ __forceinline__ uint32_t lanes_max(uint32_t v)
 {
     uint32_t t = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);    // quad_perm 1,0,3,2
     v = v > t ? v : t;
     t = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xF, 0xF, true);             // quad_perm 2,3,0,1
     v = v > t ? v : t;
     t = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x141, 0xF, 0xF, true);            // row_half_mirror: 7-i
-    return v > t ? v : t;
+    v = v > t ? v : t;
+    if constexpr (LANES >= 16) {
+        t = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x140, 0xF, 0xF, true);        // row_mirror: 15-i
+        v = v > t ? v : t;
+    }
+    if constexpr (LANES >= 32) {
+        t = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((threadIdx.x ^ 16u) << 2), (int)v);   // lane ^ 16
+        v = v > t ? v : t;
+    }
+    if constexpr (LANES >= 64) {
+        t = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((threadIdx.x ^ 32u) << 2), (int)v);   // lane ^ 32
+        v = v > t ? v : t;
+    }
+    return v;
 }
 
 // ------------------------------------------------------------------ exchange formats
@@ -132,7 +156,7 @@ struct BlockScale {
 template <int FMT>
 __device__ __forceinline__ BlockScale block_scale_from_exponent(uint32_t e_a)
 {
-    constexpr uint32_t emax = (FMT == SDL_FMT_E3M0) ? 4u : 8u;
+    constexpr uint32_t emax = is_e3m0(FMT) ? 4u : 8u;
     BlockScale b;
     b.sb = e_a > emax ? e_a - emax : 0u;
     b.degenerate = (e_a == 0u) || (e_a == 255u);
@@ -151,9 +175,10 @@ __device__ __forceinline__ float scale_from_byte(uint32_t sb)
 // Encode the lane's 4 outer gradients d of one row and one replica.  dq = decoded
 // values.  Codes: E3M0 -> c[0] holds 4 nibbles (16 bits); E4M3 -> c[0] holds 4 bytes;
 // BF16 -> c[0..1]; FP32 -> the bits of d.  sb = scale byte of the lane's block.
+// span_amax: for the whole-span scale, the bit pattern of the span's absolute maximum.
 template <int FMT>
 __device__ __forceinline__ void encode(const float (&d)[kVec], float (&dq)[kVec], uint32_t (&c)[kVec],
-                                       uint32_t& sb, bool want_codes)
+                                       uint32_t& sb, bool want_codes, uint32_t span_amax)
 {
     if constexpr (FMT == SDL_FMT_FP32) {
 #pragma unroll
@@ -174,7 +199,8 @@ __device__ __forceinline__ void encode(const float (&d)[kVec], float (&dq)[kVec]
             const uint32_t m = f2u(d[j]) & 0x7fffffffu;
             amax = m > amax ? m : amax;
         }
-        amax = block_max(amax);
+        if constexpr (is_span_scaled(FMT)) amax = span_amax;
+        else amax = lanes_max<block_elems(FMT) / kVec>(amax);
         const BlockScale b = block_scale_from_exponent<FMT>(amax >> 23);
         sb = b.sb;
         uint32_t packed = 0;
@@ -184,7 +210,7 @@ __device__ __forceinline__ void encode(const float (&d)[kVec], float (&dq)[kVec]
             const uint32_t yb = f2u(y);
             const uint32_t sign = f2u(d[j]) & 0x80000000u;
             float val;
-            if constexpr (FMT == SDL_FMT_E3M0) {
+            if constexpr (is_e3m0(FMT)) {
                 // nearest power of two in the linear domain; a tie (mantissa exactly
                 // 1.5) goes to the even exponent code, whose parity is that of the
                 // biased fp32 exponent because the re-bias (124) is even
@@ -201,7 +227,7 @@ __device__ __forceinline__ void encode(const float (&d)[kVec], float (&dq)[kVec]
             }
             dq[j] = u2f(sign | f2u(val * b.scale));
             if (want_codes) {
-                if constexpr (FMT == SDL_FMT_E3M0) {
+                if constexpr (is_e3m0(FMT)) {
                     const uint32_t E = val == 0.0f ? 0u : (f2u(val) >> 23) - 124u;
                     packed |= ((sign >> 28) | E) << (4 * j);
                 } else {
@@ -250,10 +276,43 @@ struct TileIO {
     uint64_t t0;      // tile's first element in the flat arrays (workgroup uniform)
     uint64_t tb;      // tile's first element in the message arrays (a multiple of 512)
     uint32_t lane;
+    uint32_t sidx;    // whole-span scale: index of the run's scale word
 
     static __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* p, uint32_t bytes)
     {
         return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+    }
+    // bit pattern of the span's absolute maximum (whole-span scale)
+    __device__ __forceinline__ uint32_t span_amax(uint32_t m) const
+    {
+        return reinterpret_cast<const uint32_t*>(a.scales[m])[sidx];
+    }
+    // fold a wavefront's maximum into the span's scale word
+    __device__ __forceinline__ void span_amax_update(uint32_t m, uint32_t v) const
+    {
+        uint32_t* p = reinterpret_cast<uint32_t*>(a.scales[m]) + sidx;
+        if (v > __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+            __hip_atomic_fetch_max(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    template <int FMT> __device__ __forceinline__ float load_scale(uint32_t m, int row) const
+    {
+        if constexpr (is_span_scaled(FMT)) {
+            return block_scale_from_exponent<FMT>(span_amax(m) >> 23).scale;
+        } else {
+            constexpr int B = block_elems(FMT);
+            const uint32_t sb = __builtin_amdgcn_raw_buffer_load_b8(
+                rsrc(a.scales[m] + tb / B, kGroup / B), (int)(row * (kRow / B) + lane / (B / kVec)), 0, SDL_AUX_SCALE);
+            return scale_from_byte(sb);
+        }
+    }
+    template <int FMT> __device__ __forceinline__ void store_scale(uint32_t m, int row, uint32_t sb) const
+    {
+        if constexpr (!is_span_scaled(FMT)) {
+            constexpr int B = block_elems(FMT);
+            if ((lane % (B / kVec)) == 0u)
+                __builtin_amdgcn_raw_buffer_store_b8((uint8_t)sb, rsrc(a.scales[m] + tb / B, kGroup / B),
+                                                     (int)(row * (kRow / B) + lane / (B / kVec)), 0, SDL_AUX_SCALE);
+        }
     }
     // p = address of the tile's first element in the array
     __device__ __forceinline__ void ld_f32(const float* p, int row, float (&v)[kVec]) const
@@ -299,11 +358,8 @@ struct TileIO {
             ld_bf16(reinterpret_cast<const uint16_t*>(codes) + tb, row, u);
             unpack_bf16(u, dq);
         } else {
-            const uint32_t sb = __builtin_amdgcn_raw_buffer_load_b8(
-                rsrc(a.scales[m] + tb / SDL_BLOCK, kGroup / SDL_BLOCK),
-                (int)(row * (kRow / SDL_BLOCK) + lane / kBlockLanes), 0, SDL_AUX_SCALE);
-            const float scale = scale_from_byte(sb);
-            if constexpr (FMT == SDL_FMT_E3M0) {
+            const float scale = load_scale<FMT>(m, row);
+            if constexpr (is_e3m0(FMT)) {
                 const uint32_t c0 = __builtin_amdgcn_raw_buffer_load_b16(rsrc(codes + tb / 2, kGroup / 2),
                                                                          (int)(row * (kRow / 2) + lane * 2), 0,
                                                                          SDL_AUX_LD);
@@ -328,10 +384,8 @@ struct TileIO {
             __builtin_amdgcn_raw_buffer_store_b64(x, rsrc(codes + tb * 2, kGroup * 2),
                                                   (int)(row * kRow * 2 + lane * 8), 0, SDL_AUX_ST);
         } else {
-            if ((lane % kBlockLanes) == 0u)
-                __builtin_amdgcn_raw_buffer_store_b8((uint8_t)sb, rsrc(a.scales[m] + tb / SDL_BLOCK, kGroup / SDL_BLOCK),
-                                                     (int)(row * (kRow / SDL_BLOCK) + lane / kBlockLanes), 0, SDL_AUX_SCALE);
-            if constexpr (FMT == SDL_FMT_E3M0) {
+            store_scale<FMT>(m, row, sb);
+            if constexpr (is_e3m0(FMT)) {
                 __builtin_amdgcn_raw_buffer_store_b16((uint16_t)c[0], rsrc(codes + tb / 2, kGroup / 2),
                                                       (int)(row * (kRow / 2) + lane * 2), 0, SDL_AUX_ST);
             } else {
@@ -349,6 +403,19 @@ struct GuardedIO {
     uint64_t mb;           // tile's first element in the message arrays
     uint64_t run_n;        // elements of the run
     uint32_t lane;
+    uint32_t sidx;         // whole-span scale: index of the run's scale word
+
+    __device__ __forceinline__ uint32_t span_amax(uint32_t m) const
+    {
+        return reinterpret_cast<const uint32_t*>(a.scales[m])[sidx];
+    }
+    // fold a wavefront's maximum into the span's scale word
+    __device__ __forceinline__ void span_amax_update(uint32_t m, uint32_t v) const
+    {
+        uint32_t* p = reinterpret_cast<uint32_t*>(a.scales[m]) + sidx;
+        if (v > __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+            __hip_atomic_fetch_max(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 
     // lane's first element of a row, counted from the run start, and how many of its 4 exist
     __device__ __forceinline__ uint64_t first(int row) const { return tb + (uint64_t)(row * kRow) + lane * kVec; }
@@ -409,10 +476,11 @@ struct GuardedIO {
             ld_bf16(reinterpret_cast<const uint16_t*>(codes) + b, n, u);
             unpack_bf16(u, dq);
         } else {
-            const uint32_t sb = n > 0 ? a.scales[m][b / SDL_BLOCK] : 127u;
-            const float scale = scale_from_byte(sb);
+            float scale;
+            if constexpr (is_span_scaled(FMT)) scale = block_scale_from_exponent<FMT>(span_amax(m) >> 23).scale;
+            else scale = scale_from_byte(n > 0 ? a.scales[m][b / block_elems(FMT)] : 127u);
             uint32_t c0 = 0;
-            if constexpr (FMT == SDL_FMT_E3M0) {
+            if constexpr (is_e3m0(FMT)) {
 #pragma unroll
                 for (int k = 0; k < 2; ++k)
                     if (2 * k < n) c0 |= (uint32_t)codes[b / 2 + k] << (8 * k);
@@ -440,8 +508,11 @@ struct GuardedIO {
             const uint32_t u[2] = {c[0], c[1]};
             st_bf16(reinterpret_cast<uint16_t*>(codes) + b, n, u);
         } else {
-            if ((lane % kBlockLanes) == 0u && n > 0) a.scales[m][b / SDL_BLOCK] = (uint8_t)sb;
-            if constexpr (FMT == SDL_FMT_E3M0) {
+            if constexpr (!is_span_scaled(FMT)) {
+                constexpr int B = block_elems(FMT);
+                if ((lane % (B / kVec)) == 0u && n > 0) a.scales[m][b / B] = (uint8_t)sb;
+            }
+            if constexpr (is_e3m0(FMT)) {
                 // elements beyond the end are zero outer gradients: their nibbles are 0
 #pragma unroll
                 for (int k = 0; k < 2; ++k)
@@ -477,7 +548,7 @@ __device__ __forceinline__ void process(const Args& a, const IO& io)
         if constexpr (MODE == kReduce || MODE == kFused) io.load_mom(r, mom[r]);
     }
     if constexpr (MT > 0) {
-        if constexpr (MODE == kQuantize || MODE == kFused) {
+        if constexpr (MODE == kQuantize || MODE == kFused || MODE == kAbsmax) {
 #pragma unroll
             for (int m = 0; m < MT; ++m)
 #pragma unroll
@@ -495,6 +566,29 @@ __device__ __forceinline__ void process(const Args& a, const IO& io)
 #pragma unroll
                 for (int r = 0; r < kRows; ++r) io.load_wn(m, r, wn[m][r]);
         }
+    }
+
+    // ---- pre-pass of the whole-span scale: absolute maximum of every replica's outer gradient
+    if constexpr (MODE == kAbsmax) {
+#pragma unroll
+        for (uint32_t m = 0; m < M; ++m) {
+            const int mi = MT > 0 ? (int)m : 0;
+            uint32_t amax = 0;
+#pragma unroll
+            for (int r = 0; r < kRows; ++r) {
+                if constexpr (MT == 0) io.load_ws(m, r, ws[0][r]);
+                float w[kVec];
+                unpack_bf16(ws[mi][r], w);
+#pragma unroll
+                for (int j = 0; j < kVec; ++j) {
+                    const uint32_t b = f2u(g[r][j] - w[j]) & 0x7fffffffu;
+                    amax = b > amax ? b : amax;
+                }
+            }
+            amax = lanes_max<kWave>(amax);
+            if (io.lane == 0u) io.span_amax_update(m, amax);
+        }
+        return;
     }
 
     // ---- outer gradients, messages, fp32 sum over replicas in ascending order
@@ -519,7 +613,9 @@ __device__ __forceinline__ void process(const Args& a, const IO& io)
 #pragma unroll
                     for (int j = 0; j < kVec; ++j) d[j] = g[r][j] - w[j];
                     constexpr bool want = MODE == kQuantize || EMIT;
-                    encode<FMT>(d, dq, c, sb, want);
+                    uint32_t samax = 0;
+                    if constexpr (is_span_scaled(FMT)) samax = io.span_amax(m);
+                    encode<FMT>(d, dq, c, sb, want, samax);
                     if constexpr (want) io.template store_message<FMT>(m, r, c, sb);
                 }
 #pragma unroll
@@ -593,12 +689,19 @@ void sdl_kernel(const Args a)
     const uint64_t run_n = a.runs[r].numel;
     const uint64_t tile = (uint64_t)(wg - a.runs[r].first_wg) * kGroup;   // first element of the tile in the run
     if (a.runs[r].vec && run_n - tile >= (uint64_t)kGroup) {
-        const TileIO io{a, run_off + tile, a.runs[r].msg + tile, threadIdx.x};
+        const TileIO io{a, run_off + tile, a.runs[r].msg + tile, threadIdx.x, a.runs[r].sidx};
         process<MODE, FMT, MT, ALIASED, EMIT>(a, io);
     } else {
-        const GuardedIO io{a, run_off + tile, tile, a.runs[r].msg + tile, run_n, threadIdx.x};
+        const GuardedIO io{a, run_off + tile, tile, a.runs[r].msg + tile, run_n, threadIdx.x, a.runs[r].sidx};
         process<MODE, FMT, 0, ALIASED, EMIT>(a, io);
     }
+}
+
+// Clears the scale words of a launch's runs before the whole-span maximum is accumulated.
+__global__ __launch_bounds__(SDL_MAX_WORKERS * kMaxRuns) void sdl_zero_span_scales(const Args a)
+{
+    const uint32_t m = threadIdx.x / kMaxRuns, r = threadIdx.x % kMaxRuns;
+    if (m < a.M && r < a.n_runs) reinterpret_cast<uint32_t*>(a.scales[m])[a.runs[r].sidx] = 0u;
 }
 
 // Plain streaming copy, 16 bytes per lane: the yardstick for the HBM roofline.
@@ -618,6 +721,7 @@ size_t code_align(sdl_format_t fmt)
 {
     return fmt == SDL_FMT_FP32 ? 4 : fmt == SDL_FMT_BF16 ? 2 : 1;
 }
+size_t scale_align(sdl_format_t fmt) { return is_span_scaled(fmt) ? 4 : 1; }
 // bytes of code per element (x2 for E3M0, which holds half a byte)
 size_t code_bytes_at(sdl_format_t fmt, uint64_t elem)
 {
@@ -677,15 +781,26 @@ template <int MODE>
 hipError_t launch(const Args& a, sdl_format_t fmt, uint32_t n_wg, hipStream_t s)
 {
     if constexpr (MODE == kMerge) return launch_f<MODE, SDL_FMT_FP32>(a, n_wg, s);
+    if constexpr (MODE == kQuantize || MODE == kFused) {
+        if (is_span_scaled(fmt)) {
+            // whole-span scale: clear the scale words, take the grid-wide maximum, then encode
+            hipLaunchKernelGGL(sdl_zero_span_scales, dim3(1), dim3(SDL_MAX_WORKERS * kMaxRuns), 0, s, a);
+            hipError_t e = launch_m<kAbsmax, SDL_FMT_E3M0_SPAN, false, false>(a, n_wg, s);
+            if (e != hipSuccess) return e;
+        }
+    }
     switch (fmt) {
     case SDL_FMT_FP32: return launch_f<MODE, SDL_FMT_FP32>(a, n_wg, s);
     case SDL_FMT_BF16: return launch_f<MODE, SDL_FMT_BF16>(a, n_wg, s);
     case SDL_FMT_E4M3: return launch_f<MODE, SDL_FMT_E4M3>(a, n_wg, s);
+    case SDL_FMT_E3M0_B64: return launch_f<MODE, SDL_FMT_E3M0_B64>(a, n_wg, s);
+    case SDL_FMT_E3M0_B128: return launch_f<MODE, SDL_FMT_E3M0_B128>(a, n_wg, s);
+    case SDL_FMT_E3M0_SPAN: return launch_f<MODE, SDL_FMT_E3M0_SPAN>(a, n_wg, s);
     default: return launch_f<MODE, SDL_FMT_E3M0>(a, n_wg, s);
     }
 }
 
-bool valid_format(sdl_format_t fmt) { return fmt >= SDL_FMT_FP32 && fmt <= SDL_FMT_E3M0; }
+bool valid_format(sdl_format_t fmt) { return fmt >= SDL_FMT_FP32 && fmt <= SDL_FMT_E3M0_SPAN; }
 
 // Fill a.runs from a list of (offset, numel); returns the number of workgroups.  vec is
 // set per run when every array used by the call is 16-byte aligned at the run start.
@@ -694,10 +809,11 @@ struct RunBuilder {
     uint64_t n_wg = 0;
     explicit RunBuilder(Args* args) : a(args) { a->n_runs = 0; }
     bool full() const { return a->n_runs == kMaxRuns; }
-    void add(uint64_t offset, uint64_t numel, bool vec, uint64_t msg = 0)
+    void add(uint64_t offset, uint64_t numel, bool vec, uint64_t msg = 0, uint32_t sidx = 0)
     {
         Run& r = a->runs[a->n_runs++];
         r.offset = offset; r.numel = numel; r.msg = msg; r.first_wg = (uint32_t)n_wg; r.vec = vec ? 1u : 0u;
+        r.sidx = sidx; r.pad_ = 0;
         n_wg += (numel + kGroup - 1) / kGroup;
     }
 };
@@ -722,7 +838,7 @@ int sdl_quantize_outer_grad(const float* g, const void* const* w_send, uint32_t 
                             sdl_format_t fmt, void* const* codes, void* const* scales, void* stream)
 {
     if (!valid_format(fmt) || M == 0 || M > SDL_MAX_WORKERS) return SDL_ERR_INVALID_ARG;
-    const bool scaled = fmt == SDL_FMT_E4M3 || fmt == SDL_FMT_E3M0;
+    const bool scaled = is_scaled(fmt);
     if (n && (!g || !w_send || !codes || (scaled && !scales))) return SDL_ERR_INVALID_ARG;
     if (n == 0) return SDL_OK;
     Args a;
@@ -734,6 +850,7 @@ int sdl_quantize_outer_grad(const float* g, const void* const* w_send, uint32_t 
     for (uint32_t m = 0; m < M; ++m) {
         if (!w_send[m] || !codes[m] || (scaled && !scales[m])) return SDL_ERR_INVALID_ARG;
         if (!aligned(w_send[m], 2) || !aligned(codes[m], code_align(fmt))) return SDL_ERR_ALIGNMENT;
+        if (scaled && !aligned(scales[m], scale_align(fmt))) return SDL_ERR_ALIGNMENT;
         vec = vec && aligned(w_send[m], 16) && aligned(codes[m], 16);
         a.w_send[m] = static_cast<const uint16_t*>(w_send[m]);
         a.codes[m] = static_cast<uint8_t*>(codes[m]);
@@ -747,7 +864,7 @@ int sdl_dequant_reduce_nesterov(float* g, float* mom, const void* const* codes,
                                 float lr, float mu, void* stream)
 {
     if (!valid_format(fmt) || M == 0 || M > SDL_MAX_WORKERS) return SDL_ERR_INVALID_ARG;
-    const bool scaled = fmt == SDL_FMT_E4M3 || fmt == SDL_FMT_E3M0;
+    const bool scaled = is_scaled(fmt);
     if (n && (!g || !mom || !codes || (scaled && !scales))) return SDL_ERR_INVALID_ARG;
     if (n == 0) return SDL_OK;
     if (!aligned(g, 4) || !aligned(mom, 4)) return SDL_ERR_ALIGNMENT;
@@ -758,6 +875,7 @@ int sdl_dequant_reduce_nesterov(float* g, float* mom, const void* const* codes,
     for (uint32_t m = 0; m < M; ++m) {
         if (!codes[m] || (scaled && !scales[m])) return SDL_ERR_INVALID_ARG;
         if (!aligned(codes[m], code_align(fmt))) return SDL_ERR_ALIGNMENT;
+        if (scaled && !aligned(scales[m], scale_align(fmt))) return SDL_ERR_ALIGNMENT;
         vec = vec && aligned(codes[m], 16);
         a.codes[m] = static_cast<uint8_t*>(const_cast<void*>(codes[m]));
         a.scales[m] = scaled ? static_cast<uint8_t*>(const_cast<void*>(scales[m])) : nullptr;
@@ -820,7 +938,7 @@ int sdl_fragment_outer_step(float* g, float* mom, const void* const* w_send, voi
     int rc = fill_fused_args(a, g, mom, w_send, w_now, M, fmt, lr, mu, alpha, &vec);
     if (rc != SDL_OK) return rc;
     if (codes_or_null) {
-        const bool scaled = fmt == SDL_FMT_E4M3 || fmt == SDL_FMT_E3M0;
+        const bool scaled = is_scaled(fmt);
         if (scaled && !scales_or_null) return SDL_ERR_INVALID_ARG;
         for (uint32_t m = 0; m < M; ++m) {
             if (!codes_or_null[m] || (scaled && !scales_or_null[m])) return SDL_ERR_INVALID_ARG;
@@ -830,6 +948,15 @@ int sdl_fragment_outer_step(float* g, float* mom, const void* const* w_send, voi
             a.scales[m] = scaled ? static_cast<uint8_t*>(scales_or_null[m]) : nullptr;
         }
         a.emit = 1;
+    }
+    if (is_span_scaled(fmt)) {
+        // the whole-span scale needs its 4-byte word per replica even when no message is written
+        if (!scales_or_null) return SDL_ERR_INVALID_ARG;
+        for (uint32_t m = 0; m < M; ++m) {
+            if (!scales_or_null[m]) return SDL_ERR_INVALID_ARG;
+            if (!aligned(scales_or_null[m], 4)) return SDL_ERR_ALIGNMENT;
+            a.scales[m] = static_cast<uint8_t*>(scales_or_null[m]);
+        }
     }
     return run_single_span<kFused>(a, n, fmt, vec, stream);
 }
@@ -841,19 +968,23 @@ int sdl_fragment_outer_step(float* g, float* mom, const void* const* w_send, voi
 template <int MODE>
 static int launch_fragment(Args& a, const sdl_plan_t* plan, uint32_t p, bool vec, sdl_format_t fmt, void* stream)
 {
+    // the pieces that are processed: joined runs, or, for the whole-span scale, the spans
+    // themselves (one scale word per parameter group)
     const sdl_span_t* runs = nullptr;
     uint32_t n_runs = 0;
-    int rc = sdl_plan_fragment_runs(plan, p, &runs, &n_runs);
+    int rc = is_span_scaled(fmt) && MODE != kMerge ? sdl_plan_fragment_spans(plan, p, &runs, &n_runs)
+                                                   : sdl_plan_fragment_runs(plan, p, &runs, &n_runs);
     if (rc != SDL_OK) return rc;
     uint64_t msg = 0;
     for (uint32_t first = 0; first < n_runs; first += kMaxRuns) {
         RunBuilder rb(&a);
         for (uint32_t i = first; i < n_runs && i < first + kMaxRuns; ++i) {
             // a run keeps the 16-byte alignment of the bases when it starts on a multiple of 8 elements
-            rb.add(runs[i].offset, runs[i].numel, vec && (runs[i].offset % 8 == 0), msg);
+            rb.add(runs[i].offset, runs[i].numel, vec && (runs[i].offset % 8 == 0), msg, i);
             msg += (runs[i].numel + kGroup - 1) / kGroup * kGroup;
         }
         if (rb.n_wg > 0x7fffffffull) return SDL_ERR_UNSUPPORTED;
+        if (rb.n_wg == 0) continue;
         hipError_t e = launch<MODE>(a, fmt, (uint32_t)rb.n_wg, (hipStream_t)stream);
         if (e != hipSuccess) return SDL_ERR_DEVICE;
     }
@@ -865,14 +996,16 @@ extern "C" {
 int sdl_plan_message_bytes(const sdl_plan_t* plan, uint32_t p, sdl_format_t fmt, size_t* code_bytes,
                            size_t* scale_bytes)
 {
+    if (!valid_format(fmt)) return SDL_ERR_INVALID_ARG;
     const sdl_span_t* runs = nullptr;
     uint32_t n_runs = 0;
-    int rc = sdl_plan_fragment_runs(plan, p, &runs, &n_runs);
+    int rc = is_span_scaled(fmt) ? sdl_plan_fragment_spans(plan, p, &runs, &n_runs)
+                                 : sdl_plan_fragment_runs(plan, p, &runs, &n_runs);
     if (rc != SDL_OK) return rc;
-    if (!valid_format(fmt)) return SDL_ERR_INVALID_ARG;
     uint64_t padded = 0;
     for (uint32_t i = 0; i < n_runs; ++i) padded += (runs[i].numel + kGroup - 1) / kGroup * kGroup;
     sdl_exchange_bytes(fmt, padded, code_bytes, scale_bytes);
+    if (is_span_scaled(fmt) && scale_bytes) *scale_bytes = (size_t)n_runs * 4;   // one word per span
     return SDL_OK;
 }
 
@@ -881,6 +1014,9 @@ int sdl_fragment_outer_step_plan(const sdl_plan_t* plan, uint32_t p, float* g_ba
                                  sdl_format_t fmt, float lr, float mu, float alpha, void* stream)
 {
     if (!plan || p >= sdl_plan_num_fragments(plan)) return SDL_ERR_INVALID_ARG;
+    // the whole-span scale needs scale words, which this call has no argument for: use the
+    // fragment-level send / receive calls (or the span-level fused call) instead
+    if (is_span_scaled(fmt)) return SDL_ERR_UNSUPPORTED;
     Args a;
     bool vec = false;
     int rc = fill_fused_args(a, g_base, mom_base, w_send_base, w_now_base, M, fmt, lr, mu, alpha, &vec);
@@ -894,7 +1030,7 @@ int sdl_quantize_outer_grad_plan(const sdl_plan_t* plan, uint32_t p, const float
 {
     if (!plan || p >= sdl_plan_num_fragments(plan)) return SDL_ERR_INVALID_ARG;
     if (!valid_format(fmt) || M == 0 || M > SDL_MAX_WORKERS) return SDL_ERR_INVALID_ARG;
-    const bool scaled = fmt == SDL_FMT_E4M3 || fmt == SDL_FMT_E3M0;
+    const bool scaled = is_scaled(fmt);
     if (!g_base || !w_send_base || !codes || (scaled && !scales)) return SDL_ERR_INVALID_ARG;
     if (!aligned(g_base, 4)) return SDL_ERR_ALIGNMENT;
     Args a;
@@ -905,6 +1041,7 @@ int sdl_quantize_outer_grad_plan(const sdl_plan_t* plan, uint32_t p, const float
     for (uint32_t m = 0; m < M; ++m) {
         if (!w_send_base[m] || !codes[m] || (scaled && !scales[m])) return SDL_ERR_INVALID_ARG;
         if (!aligned(w_send_base[m], 2) || !aligned(codes[m], code_align(fmt))) return SDL_ERR_ALIGNMENT;
+        if (scaled && !aligned(scales[m], scale_align(fmt))) return SDL_ERR_ALIGNMENT;
         vec = vec && aligned(w_send_base[m], 16) && aligned(codes[m], 16);
         a.w_send[m] = static_cast<const uint16_t*>(w_send_base[m]);
         a.codes[m] = static_cast<uint8_t*>(codes[m]);
@@ -919,7 +1056,7 @@ int sdl_dequant_reduce_nesterov_plan(const sdl_plan_t* plan, uint32_t p, float* 
 {
     if (!plan || p >= sdl_plan_num_fragments(plan)) return SDL_ERR_INVALID_ARG;
     if (!valid_format(fmt) || M == 0 || M > SDL_MAX_WORKERS) return SDL_ERR_INVALID_ARG;
-    const bool scaled = fmt == SDL_FMT_E4M3 || fmt == SDL_FMT_E3M0;
+    const bool scaled = is_scaled(fmt);
     if (!g_base || !mom_base || !codes || (scaled && !scales)) return SDL_ERR_INVALID_ARG;
     if (!aligned(g_base, 4) || !aligned(mom_base, 4)) return SDL_ERR_ALIGNMENT;
     Args a;
@@ -929,6 +1066,7 @@ int sdl_dequant_reduce_nesterov_plan(const sdl_plan_t* plan, uint32_t p, float* 
     for (uint32_t m = 0; m < M; ++m) {
         if (!codes[m] || (scaled && !scales[m])) return SDL_ERR_INVALID_ARG;
         if (!aligned(codes[m], code_align(fmt))) return SDL_ERR_ALIGNMENT;
+        if (scaled && !aligned(scales[m], scale_align(fmt))) return SDL_ERR_ALIGNMENT;
         vec = vec && aligned(codes[m], 16);
         a.codes[m] = static_cast<uint8_t*>(const_cast<void*>(codes[m]));
         a.scales[m] = scaled ? static_cast<uint8_t*>(const_cast<void*>(scales[m])) : nullptr;

@@ -29,8 +29,8 @@ uint32_t owner_of_block(uint32_t i, uint32_t L, uint32_t P, sdl_pattern_t patter
 
 // Join neighbouring spans into runs.  A span may be appended to the current run only
 // if it starts where the run ends and the run's length so far is a multiple of the
-// scale-block size, so that block boundaries counted from the run start coincide with
-// those counted from each span start.
+// largest scale-block size (128), so that block boundaries counted from the run start
+// coincide with those counted from each span start for every block-scaled format.
 std::vector<sdl_span_t> join_spans(const std::vector<sdl_span_t>& spans)
 {
     std::vector<sdl_span_t> runs;
@@ -38,7 +38,7 @@ std::vector<sdl_span_t> join_spans(const std::vector<sdl_span_t>& spans)
         if (s.numel == 0) continue;
         if (!runs.empty()) {
             sdl_span_t& r = runs.back();
-            if (r.offset + r.numel == s.offset && r.numel % SDL_BLOCK == 0) {
+            if (r.offset + r.numel == s.offset && r.numel % SDL_MAX_BLOCK == 0) {
                 r.numel += s.numel;
                 continue;
             }
@@ -175,6 +175,9 @@ size_t sdl_exchange_bytes(sdl_format_t fmt, uint64_t numel, size_t* code_bytes, 
     case SDL_FMT_BF16: c = (size_t)numel * 2; break;
     case SDL_FMT_E4M3: c = (size_t)numel; s = blocks; break;
     case SDL_FMT_E3M0: c = (size_t)((numel + 1) / 2); s = blocks; break;
+    case SDL_FMT_E3M0_B64: c = (size_t)((numel + 1) / 2); s = (size_t)((numel + 63) / 64); break;
+    case SDL_FMT_E3M0_B128: c = (size_t)((numel + 1) / 2); s = (size_t)((numel + 127) / 128); break;
+    case SDL_FMT_E3M0_SPAN: c = (size_t)((numel + 1) / 2); s = numel ? 4 : 0; break;
     default: break;
     }
     if (code_bytes) *code_bytes = c;

@@ -12,7 +12,7 @@ import paper_2501_18512_amd as sdl
 import workloads
 
 RTOL, ATOL = 1e-6, 1e-7
-FMT_NAMES = {0: "fp32", 1: "bf16", 2: "e4m3", 3: "e3m0"}
+FMT_NAMES = {0: "fp32", 1: "bf16", 2: "e4m3", 3: "e3m0", 4: "e3m0_b64", 5: "e3m0_b128", 6: "e3m0_span"}
 
 
 def host_f32(t):
@@ -83,6 +83,8 @@ def check_fused_against_oracle(g, mom, w_send, w_now, fmt, lr, mu, alpha, *, emi
     codes = scales = None
     if emit:
         codes, scales = sdl.alloc_exchange(fmt, n, len(w_send), device=g.device)
+    elif fmt == sdl.FMT_E3M0_SPAN:
+        scales = sdl.alloc_exchange(fmt, n, len(w_send), device=g.device)[1]   # workspace for the span maximum
     sdl.sdl_fragment_outer_step(g, mom, w_send, w_now, n, fmt, lr, mu, alpha, codes, scales)
     torch.cuda.synchronize()
     if emit:

@@ -34,6 +34,9 @@ def _small_model(seed=0):
     ((1, 4), 2, sdl.PATTERN_SEQUENTIAL, sdl.FMT_E4M3),     # slack between workers
     ((0, 3, 2), 7, sdl.PATTERN_STRIDED, sdl.FMT_BF16),
     ((2, 2), 1, sdl.PATTERN_STRIDED, sdl.FMT_FP32),        # P = 1: DiLoCo with overlap
+    ((1, 1), 3, sdl.PATTERN_STRIDED, sdl.FMT_E3M0_SPAN),   # one scale per tensor (4.0 bits / parameter)
+    ((0, 0), 2, sdl.PATTERN_STRIDED, sdl.FMT_E3M0_SPAN),
+    ((1, 2), 2, sdl.PATTERN_STRIDED, sdl.FMT_E3M0_B128),
 ])
 def test_engine_matches_oracle_walk(taus, P, pattern, fmt):
     H, T, M = 12, 3 * 12 + 9, len(taus)

@@ -57,10 +57,10 @@ def test_plan_matches_oracle(shape, P, pattern, H, tau, t_p):
         assert sum(n for _, n, _ in runs) == sum(n for _, n, _ in ref.spans[p])
         covered = sorted((off, off + n) for off, n, _ in runs)
         for (a0, a1), (b0, b1) in zip(covered, covered[1:]):
-            assert a1 < b0 or (a1 == b0 and (a1 - a0) % 32 != 0)     # otherwise it should have been joined
+            assert a1 < b0 or (a1 == b0 and (a1 - a0) % 128 != 0)    # otherwise it should have been joined
         starts = {off for off, _, _ in ref.spans[p]}
         for off, n, _ in runs:                                       # every span start inside a run is block aligned
-            assert all((s - off) % 32 == 0 for s in starts if off <= s < off + n)
+            assert all((s - off) % 128 == 0 for s in starts if off <= s < off + n)
     for t in range(1, 3 * H + tau + 2):
         assert sdl.sdl_plan_events(plan, t) == (ref.sends(t), ref.receives(t))
 
@@ -87,12 +87,15 @@ def test_plan_with_embedding_fragment_matches_oracle(shape, P, pattern, H):
 
 
 def test_runs_respect_ragged_spans():
-    # adjacent spans are joined only while the run so far is a whole number of scale blocks
-    plan = sdl.sdl_fragment_plan([40, 24, 64, 32], [0, 0, 0, 0], 1, 1)
-    assert sdl.sdl_plan_fragment_runs(plan, 0) == [(0, 40, 0), (40, 24, 1), (64, 64 + 32, 2)]
-    plan = sdl.sdl_fragment_plan([64, 0, 32, 5, 3], [0, 1, 0, 0, 0], 2, 2)
-    assert sdl.sdl_plan_fragment_runs(plan, 0) == [(0, 64 + 32 + 5, 0), (101, 3, 4)]
+    # adjacent spans are joined only while the run so far is a whole number of the largest
+    # scale block (128 elements)
+    plan = sdl.sdl_fragment_plan([40, 24, 128, 256, 32], [0, 0, 0, 0, 0], 1, 1)
+    assert sdl.sdl_plan_fragment_runs(plan, 0) == [(0, 40, 0), (40, 24, 1), (64, 128 + 256 + 32, 2)]
+    plan = sdl.sdl_fragment_plan([256, 0, 128, 5, 3], [0, 1, 0, 0, 0], 2, 2)
+    assert sdl.sdl_plan_fragment_runs(plan, 0) == [(0, 256 + 128 + 5, 0), (389, 3, 4)]
     assert sdl.sdl_plan_fragment_runs(plan, 1) == []
+    plan = sdl.sdl_fragment_plan([64, 64], [0, 0], 1, 1)
+    assert sdl.sdl_plan_fragment_runs(plan, 0) == [(0, 64, 0), (64, 64, 1)]
 
 
 @pytest.mark.parametrize("kwargs", [
@@ -109,8 +112,8 @@ def test_plan_rejects_bad_arguments(kwargs):
 
 
 def test_exchange_bytes():
-    for fmt in range(4):
-        for n in (0, 1, 2, 31, 32, 33, 1 << 20, 4273695744):
+    for fmt in range(7):
+        for n in (0, 1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 1 << 20, 4273695744):
             assert sdl.sdl_exchange_bytes(fmt, n) == oracle.exchange_bytes(fmt, n)
 
 
@@ -164,3 +167,5 @@ def test_engine_rejects_bad_arguments():
     with pytest.raises(sdl.SdlError):
         sdl.sdl_engine_bind(eng, 0x1000, 0x1000, [0x1000, 0x1000], None, None)      # overlap needs message buffers
     assert sdl.sdl_plan_message_bytes(plan, 0, sdl.FMT_E3M0) == (2 * 512 // 2, 2 * 512 // 32)
+    assert sdl.sdl_plan_message_bytes(plan, 0, sdl.FMT_E3M0_B128) == (2 * 512 // 2, 2 * 512 // 128)
+    assert sdl.sdl_plan_message_bytes(plan, 0, sdl.FMT_E3M0_SPAN) == (2 * 512 // 2, 2 * 4)
