@@ -254,6 +254,58 @@ int sdl_engine_bind(sdl_engine_t* engine, float* g_base, float* mom_base, void* 
                     void* const* codes, void* const* scales);
 int sdl_engine_step(sdl_engine_t* engine, uint64_t t, void* stream, uint32_t* n_sent, uint32_t* n_received);
 
+/* ------------------------------------------------------------------ outer state in host memory
+ *
+ * Section 2.5: only the fragment being synchronised needs its outer parameters and Nesterov
+ * state in HBM (two words per parameter of the fragment); the rest can live in host memory,
+ * and because the schedule is known in advance a fragment can be copied in ahead of time.
+ *
+ * "Staged" forms of the fragment-level calls: g_frag / mom_frag point at a device buffer that
+ * holds only fragment p, its runs back to back, each padded to a multiple of 512 elements
+ * (sdl_plan_staged_numel elements in all); the replicas stay flat model arrays. */
+uint64_t sdl_plan_staged_numel(const sdl_plan_t* plan, uint32_t p);
+int sdl_fragment_outer_step_staged(const sdl_plan_t* plan, uint32_t p, float* g_frag, float* mom_frag,
+                                   const void* const* w_send_base, void* const* w_now_base, uint32_t M,
+                                   sdl_format_t fmt, float lr, float mu, float alpha, void* stream);
+int sdl_quantize_outer_grad_staged(const sdl_plan_t* plan, uint32_t p, const float* g_frag,
+                                   const void* const* w_send_base, uint32_t M, sdl_format_t fmt,
+                                   void* const* codes, void* const* scales, void* stream);
+int sdl_dequant_reduce_nesterov_staged(const sdl_plan_t* plan, uint32_t p, float* g_frag, float* mom_frag,
+                                       const void* const* codes, const void* const* scales, uint32_t M,
+                                       sdl_format_t fmt, float lr, float mu, void* stream);
+int sdl_merge_overlap_staged(const sdl_plan_t* plan, uint32_t p, const float* g_new_frag, void* const* w_now_base,
+                             uint32_t M, float alpha, void* stream);
+
+/* The staging pool.  g_host / mom_host: the whole model's outer parameters and momentum in
+ * host memory (flat layout; pinned memory makes the copies asynchronous).  slot_g / slot_mom:
+ * n_slots device buffers of sdl_offload_slot_numel() floats each, 16-byte aligned.  All
+ * memory is the caller's.
+ *   prefetch  starts the host-to-device copy of fragment p into a free slot on copy_stream
+ *             (SDL_ERR_NOMEM if every slot is taken; no-op if p is already staged)
+ *   acquire   prefetch if needed, make compute_stream wait for the copy, return the slot
+ *   release   after the work queued on compute_stream: copy the fragment back to the host
+ *             arrays on copy_stream and free the slot
+ *   flush     write every staged fragment back without freeing its slot (checkpointing)
+ * The same copy_stream must be used for all calls on one pool (write-back and the next
+ * copy-in of a slot are ordered by it).  Host arrays are valid after the copy stream has
+ * been synchronised.  sdl_engine_bind_offload makes an engine take g / mom from the pool
+ * instead of flat device arrays; it prefetches the fragments that send within `lookahead`
+ * steps. */
+typedef struct sdl_offload sdl_offload_t;
+int sdl_offload_create(const sdl_plan_t* plan, uint32_t n_slots, sdl_offload_t** out);
+void sdl_offload_destroy(sdl_offload_t* pool);
+uint64_t sdl_offload_slot_numel(const sdl_offload_t* pool);
+int sdl_offload_bind(sdl_offload_t* pool, float* g_host, float* mom_host, float* const* slot_g,
+                     float* const* slot_mom);
+int sdl_offload_resident(const sdl_offload_t* pool, uint32_t p);
+int sdl_offload_prefetch(sdl_offload_t* pool, uint32_t p, void* copy_stream);
+int sdl_offload_acquire(sdl_offload_t* pool, uint32_t p, void* compute_stream, void* copy_stream,
+                        float** g_frag, float** mom_frag);
+int sdl_offload_release(sdl_offload_t* pool, uint32_t p, void* compute_stream, void* copy_stream);
+int sdl_offload_flush(sdl_offload_t* pool, void* compute_stream, void* copy_stream);
+int sdl_engine_bind_offload(sdl_engine_t* engine, sdl_offload_t* pool, void* const* w_base, void* const* codes,
+                            void* const* scales, void* copy_stream, uint32_t lookahead);
+
 /* Plain device-to-device streaming copy of nbytes (a multiple of 16; both pointers
  * 16-byte aligned).  Not part of the method: it is the yardstick against which the
  * achieved memory bandwidth of the calls above is judged (2 * nbytes of traffic). */

@@ -82,6 +82,24 @@ def _load() -> ctypes.CDLL:
     lib.sdl_engine_destroy.restype = None
     lib.sdl_engine_bind.argtypes = [vp, vp, vp, pp, pp, pp]
     lib.sdl_engine_step.argtypes = [vp, u64, vp, ctypes.POINTER(u32), ctypes.POINTER(u32)]
+    lib.sdl_plan_staged_numel.argtypes = [vp, u32]
+    lib.sdl_plan_staged_numel.restype = u64
+    lib.sdl_fragment_outer_step_staged.argtypes = lib.sdl_fragment_outer_step_plan.argtypes
+    lib.sdl_quantize_outer_grad_staged.argtypes = lib.sdl_quantize_outer_grad_plan.argtypes
+    lib.sdl_dequant_reduce_nesterov_staged.argtypes = lib.sdl_dequant_reduce_nesterov_plan.argtypes
+    lib.sdl_merge_overlap_staged.argtypes = lib.sdl_merge_overlap_plan.argtypes
+    lib.sdl_offload_create.argtypes = [vp, u32, ctypes.POINTER(vp)]
+    lib.sdl_offload_destroy.argtypes = [vp]
+    lib.sdl_offload_destroy.restype = None
+    lib.sdl_offload_slot_numel.argtypes = [vp]
+    lib.sdl_offload_slot_numel.restype = u64
+    lib.sdl_offload_bind.argtypes = [vp, vp, vp, pp, pp]
+    lib.sdl_offload_resident.argtypes = [vp, u32]
+    lib.sdl_offload_prefetch.argtypes = [vp, u32, vp]
+    lib.sdl_offload_acquire.argtypes = [vp, u32, vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp)]
+    lib.sdl_offload_release.argtypes = [vp, u32, vp, vp]
+    lib.sdl_offload_flush.argtypes = [vp, vp, vp]
+    lib.sdl_engine_bind_offload.argtypes = [vp, vp, pp, pp, pp, vp, u32]
     lib.sdl_copy_bytes.argtypes = [vp, vp, u64, vp]
     lib.sdl_status_string.argtypes = [ctypes.c_int]
     lib.sdl_status_string.restype = ctypes.c_char_p
@@ -339,6 +357,91 @@ def sdl_engine_step(engine: Engine, t: int, stream=None) -> Tuple[int, int]:
     _check(_lib.sdl_engine_step(engine._h, t, _stream(stream), ctypes.byref(ns), ctypes.byref(nr)),
            "sdl_engine_step")
     return ns.value, nr.value
+
+
+# ------------------------------------------------------------- outer state in host memory
+
+def sdl_plan_staged_numel(plan: Plan, p: int) -> int:
+    return _lib.sdl_plan_staged_numel(plan._h, p)
+
+
+def sdl_fragment_outer_step_staged(plan: Plan, p: int, g_frag, mom_frag, w_send_base, w_now_base, fmt: int,
+                                   lr: float, mu: float, alpha: float, stream=None):
+    _require_device(g_frag, mom_frag, *w_send_base, *w_now_base)
+    _check(_lib.sdl_fragment_outer_step_staged(plan._h, p, _ptr(g_frag), _ptr(mom_frag), _ptr_array(w_send_base),
+                                               _ptr_array(w_now_base), len(w_send_base), fmt, lr, mu, alpha,
+                                               _stream(stream)), "sdl_fragment_outer_step_staged")
+
+
+class Offload:
+    """Owner of an sdl_offload_t handle (keeps the plan and the bound tensors alive)."""
+
+    def __init__(self, handle: int, plan: Plan):
+        self._h = ctypes.c_void_p(handle)
+        self._plan = plan
+        self._keep = None
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.sdl_offload_destroy(self._h)
+            self._h = None
+
+    @property
+    def slot_numel(self) -> int:
+        return _lib.sdl_offload_slot_numel(self._h)
+
+
+def sdl_offload_create(plan: Plan, n_slots: int) -> Offload:
+    out = ctypes.c_void_p()
+    _check(_lib.sdl_offload_create(plan._h, n_slots, ctypes.byref(out)), "sdl_offload_create")
+    return Offload(out.value, plan)
+
+
+def sdl_offload_bind(pool: Offload, g_host, mom_host, slot_g, slot_mom):
+    """g_host / mom_host: host tensors (pinned for asynchronous copies); slot_*: device tensors."""
+    for t in (g_host, mom_host):
+        if isinstance(t, torch.Tensor) and (t.is_cuda or not t.is_contiguous()):
+            raise ValueError("the offloaded outer state lives in contiguous host tensors")
+    _require_device(*slot_g, *slot_mom)
+    _check(_lib.sdl_offload_bind(pool._h, _ptr(g_host), _ptr(mom_host), _ptr_array(slot_g), _ptr_array(slot_mom)),
+           "sdl_offload_bind")
+    pool._keep = (g_host, mom_host, list(slot_g), list(slot_mom))
+
+
+def sdl_offload_resident(pool: Offload, p: int) -> bool:
+    rc = _lib.sdl_offload_resident(pool._h, p)
+    if rc < 0:
+        raise SdlError(rc, "sdl_offload_resident")
+    return bool(rc)
+
+
+def sdl_offload_prefetch(pool: Offload, p: int, copy_stream):
+    _check(_lib.sdl_offload_prefetch(pool._h, p, _stream(copy_stream)), "sdl_offload_prefetch")
+
+
+def sdl_offload_acquire(pool: Offload, p: int, copy_stream, stream=None) -> Tuple[int, int]:
+    """Returns the device addresses (g_frag, mom_frag) of the slot that holds fragment p."""
+    g, m = ctypes.c_void_p(), ctypes.c_void_p()
+    _check(_lib.sdl_offload_acquire(pool._h, p, _stream(stream), _stream(copy_stream), ctypes.byref(g),
+                                    ctypes.byref(m)), "sdl_offload_acquire")
+    return g.value, m.value
+
+
+def sdl_offload_release(pool: Offload, p: int, copy_stream, stream=None):
+    _check(_lib.sdl_offload_release(pool._h, p, _stream(stream), _stream(copy_stream)), "sdl_offload_release")
+
+
+def sdl_offload_flush(pool: Offload, copy_stream, stream=None):
+    _check(_lib.sdl_offload_flush(pool._h, _stream(stream), _stream(copy_stream)), "sdl_offload_flush")
+
+
+def sdl_engine_bind_offload(engine: Engine, pool: Offload, w_base, codes=None, scales=None, copy_stream=None,
+                            lookahead: int = 1):
+    _require_device(*w_base, *(codes or []), *(scales or []))
+    _check(_lib.sdl_engine_bind_offload(engine._h, pool._h, _ptr_array(w_base), _ptr_array(codes),
+                                        _ptr_array(scales), _stream(copy_stream), lookahead),
+           "sdl_engine_bind_offload")
+    engine._keep = (pool, list(w_base), codes, scales, copy_stream)
 
 
 def sdl_copy_bytes(dst, src, nbytes: int, stream=None):

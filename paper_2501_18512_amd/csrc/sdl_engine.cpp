@@ -22,6 +22,10 @@ struct sdl_engine {
     std::vector<void*> w;                // M live replicas
     std::vector<void*> codes, scales;    // P*M message buffers (index p*M + m); unused when all delays are 0
     bool bound = false;
+    // outer state in host memory: fragments are staged through `offload` (may be null)
+    sdl_offload_t* offload = nullptr;
+    void* copy_stream = nullptr;
+    uint32_t lookahead = 0;
     // per fragment: step at which the message in flight was sent (0 = none), reduce done?, merged[m]
     std::vector<uint64_t> sent_at;
     std::vector<uint8_t> reduced;
@@ -93,27 +97,59 @@ int sdl_engine_bind(sdl_engine_t* e, float* g_base, float* mom_base, void* const
     return SDL_OK;
 }
 
+int sdl_engine_bind_offload(sdl_engine_t* e, sdl_offload_t* offload, void* const* w_base, void* const* codes,
+                            void* const* scales, void* copy_stream, uint32_t lookahead)
+{
+    if (!e || !offload) return SDL_ERR_INVALID_ARG;
+    // the flat g / mom pointers are never dereferenced in this mode: a non-null placeholder
+    static float placeholder;
+    int rc = sdl_engine_bind(e, &placeholder, &placeholder, w_base, codes, scales);
+    if (rc != SDL_OK) return rc;
+    e->g = e->mom = nullptr;
+    e->offload = offload;
+    e->copy_stream = copy_stream;
+    e->lookahead = lookahead;
+    return SDL_OK;
+}
+
 int sdl_engine_step(sdl_engine_t* e, uint64_t t, void* stream, uint32_t* n_sent, uint32_t* n_received)
 {
     if (!e || !e->bound || t == 0) return SDL_ERR_INVALID_ARG;
     uint32_t sent = 0, received = 0;
     const uint32_t M = e->M;
+    const bool staged = e->offload != nullptr;
     for (uint32_t p = 0; p < e->P; ++p) {
         void* const* codes = e->codes.data() + (size_t)p * M;
         void* const* scales = e->scales.data() + (size_t)p * M;
+        float* g = e->g;
+        float* mom = e->mom;
         // ---- send side: t = t_p + k*H, k >= 1
         const uint64_t s0 = e->offset[p];
-        if (t > s0 && (t - s0) % e->H == 0) {
+        const bool sends = t > s0 && (t - s0) % e->H == 0;
+        if (staged && (sends || e->sent_at[p] != 0)) {
+            // outer state of this fragment comes from its staging slot (copied in on demand if
+            // it was not prefetched); the compute stream waits for the copy
+            int rc = sdl_offload_acquire(e->offload, p, stream, e->copy_stream, &g, &mom);
+            if (rc != SDL_OK) return rc;
+        }
+        if (sends) {
             if (e->sent_at[p] != 0) return SDL_ERR_INVALID_ARG;      // previous message not consumed: steps skipped
             if (e->delay_max == 0 && e->fmt != SDL_FMT_E3M0_SPAN) {
                 // no overlap anywhere: the whole outer step at once
-                int rc = sdl_fragment_outer_step_plan(e->plan, p, e->g, e->mom, e->w.data(), e->w.data(), M, e->fmt,
-                                                      e->lr, e->mu, e->alpha, stream);
+                int rc = staged ? sdl_fragment_outer_step_staged(e->plan, p, g, mom, e->w.data(), e->w.data(), M,
+                                                                 e->fmt, e->lr, e->mu, e->alpha, stream)
+                                : sdl_fragment_outer_step_plan(e->plan, p, g, mom, e->w.data(), e->w.data(), M,
+                                                               e->fmt, e->lr, e->mu, e->alpha, stream);
                 if (rc != SDL_OK) return rc;
+                if (staged) {
+                    rc = sdl_offload_release(e->offload, p, stream, e->copy_stream);
+                    if (rc != SDL_OK) return rc;
+                }
                 ++sent; ++received;
                 continue;
             }
-            int rc = sdl_quantize_outer_grad_plan(e->plan, p, e->g, e->w.data(), M, e->fmt, codes, scales, stream);
+            int rc = staged ? sdl_quantize_outer_grad_staged(e->plan, p, g, e->w.data(), M, e->fmt, codes, scales, stream)
+                            : sdl_quantize_outer_grad_plan(e->plan, p, g, e->w.data(), M, e->fmt, codes, scales, stream);
             if (rc != SDL_OK) return rc;
             e->sent_at[p] = t;
             e->reduced[p] = 0;
@@ -124,8 +160,10 @@ int sdl_engine_step(sdl_engine_t* e, uint64_t t, void* stream, uint32_t* n_sent,
         if (e->sent_at[p] != 0) {
             const uint64_t ts = e->sent_at[p];
             if (!e->reduced[p] && t == ts + e->delay_min) {
-                int rc = sdl_dequant_reduce_nesterov_plan(e->plan, p, e->g, e->mom, codes, scales, M, e->fmt, e->lr,
-                                                          e->mu, stream);
+                int rc = staged ? sdl_dequant_reduce_nesterov_staged(e->plan, p, g, mom, codes, scales, M, e->fmt,
+                                                                     e->lr, e->mu, stream)
+                                : sdl_dequant_reduce_nesterov_plan(e->plan, p, g, mom, codes, scales, M, e->fmt,
+                                                                   e->lr, e->mu, stream);
                 if (rc != SDL_OK) return rc;
                 e->reduced[p] = 1;
                 ++received;
@@ -140,11 +178,33 @@ int sdl_engine_step(sdl_engine_t* e, uint64_t t, void* stream, uint32_t* n_sent,
             }
             if (n_due) {
                 if (!e->reduced[p]) return SDL_ERR_INVALID_ARG;
-                int rc = sdl_merge_overlap_plan(e->plan, p, e->g, due, n_due, e->alpha, stream);
+                int rc = staged ? sdl_merge_overlap_staged(e->plan, p, g, due, n_due, e->alpha, stream)
+                                : sdl_merge_overlap_plan(e->plan, p, g, due, n_due, e->alpha, stream);
                 if (rc != SDL_OK) return rc;
             }
-            if (n_done == M) e->sent_at[p] = 0;
-            else if (t > ts + e->delay_max) return SDL_ERR_INVALID_ARG;   // steps were skipped
+            if (n_done == M) {
+                e->sent_at[p] = 0;
+                if (staged) {
+                    // synchronisation of this fragment is complete: write its outer state back
+                    int rc = sdl_offload_release(e->offload, p, stream, e->copy_stream);
+                    if (rc != SDL_OK) return rc;
+                }
+            } else if (t > ts + e->delay_max) {
+                return SDL_ERR_INVALID_ARG;   // steps were skipped
+            }
+        }
+    }
+    if (staged) {
+        // the schedule is known in advance: start copying in the fragments that send within the
+        // next `lookahead` steps (a full pool of slots just means they are fetched on demand)
+        for (uint32_t p = 0; p < e->P && e->lookahead > 0; ++p) {
+            const uint64_t s0 = e->offset[p];
+            const uint64_t k = t >= s0 ? (t - s0) / e->H + 1 : 1;     // next send strictly after t
+            const uint64_t next = s0 + k * e->H;
+            if (next - t <= e->lookahead && e->sent_at[p] == 0) {
+                int rc = sdl_offload_prefetch(e->offload, p, e->copy_stream);
+                if (rc != SDL_OK && rc != SDL_ERR_NOMEM) return rc;
+            }
         }
     }
     if (n_sent) *n_sent = sent;

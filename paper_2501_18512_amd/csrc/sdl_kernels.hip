@@ -52,6 +52,7 @@ struct Run {
     uint64_t offset;     // first element of the run in the flat arrays
     uint64_t numel;
     uint64_t msg;        // where the run starts in the message arrays, in elements (a multiple of 512)
+    uint64_t soff;       // where the run starts in staged g / mom arrays, in elements (staged state only)
     uint32_t first_wg;   // first workgroup of the launch that works on this run
     uint32_t vec;        // 1: every array of this run is 16-byte aligned at its start
     uint32_t sidx;       // whole-span scale: index of the run's 4-byte scale word
@@ -71,6 +72,7 @@ struct Args {
     float lr, mu, alpha, one_minus_alpha;
     uint32_t aliased;    // w_send[m] == w_now[m]
     uint32_t emit;       // fused kernel: also write the messages
+    uint32_t staged;     // g / mom point at a staging buffer that holds only this fragment
 };
 
 // Cache policy bits of the buffer instructions on gfx950: 1 = sc0, 2 = nt, 16 = sc1.
@@ -277,6 +279,7 @@ struct TileIO {
     uint64_t tb;      // tile's first element in the message arrays (a multiple of 512)
     uint32_t lane;
     uint32_t sidx;    // whole-span scale: index of the run's scale word
+    uint64_t s0;      // tile's first element in g / mom (= t0 unless the state is staged)
 
     static __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* p, uint32_t bytes)
     {
@@ -340,10 +343,10 @@ struct TileIO {
                                               SDL_AUX_ST);
     }
 
-    __device__ __forceinline__ void load_g(int row, float (&v)[kVec]) const { ld_f32(a.g + t0, row, v); }
-    __device__ __forceinline__ void load_mom(int row, float (&v)[kVec]) const { ld_f32(a.mom + t0, row, v); }
-    __device__ __forceinline__ void store_g(int row, const float (&v)[kVec]) const { st_f32(a.g + t0, row, v); }
-    __device__ __forceinline__ void store_mom(int row, const float (&v)[kVec]) const { st_f32(a.mom + t0, row, v); }
+    __device__ __forceinline__ void load_g(int row, float (&v)[kVec]) const { ld_f32(a.g + s0, row, v); }
+    __device__ __forceinline__ void load_mom(int row, float (&v)[kVec]) const { ld_f32(a.mom + s0, row, v); }
+    __device__ __forceinline__ void store_g(int row, const float (&v)[kVec]) const { st_f32(a.g + s0, row, v); }
+    __device__ __forceinline__ void store_mom(int row, const float (&v)[kVec]) const { st_f32(a.mom + s0, row, v); }
     __device__ __forceinline__ void load_ws(uint32_t m, int row, uint32_t (&u)[2]) const { ld_bf16(a.w_send[m] + t0, row, u); }
     __device__ __forceinline__ void load_wn(uint32_t m, int row, uint32_t (&u)[2]) const { ld_bf16(a.w_now[m] + t0, row, u); }
     __device__ __forceinline__ void store_wn(uint32_t m, int row, const uint32_t (&u)[2]) const { st_bf16(a.w_now[m] + t0, row, u); }
@@ -404,6 +407,7 @@ struct GuardedIO {
     uint64_t run_n;        // elements of the run
     uint32_t lane;
     uint32_t sidx;         // whole-span scale: index of the run's scale word
+    uint64_t s0;           // tile's first element in g / mom (= t0 unless the state is staged)
 
     __device__ __forceinline__ uint32_t span_amax(uint32_t m) const
     {
@@ -426,6 +430,7 @@ struct GuardedIO {
     }
     __device__ __forceinline__ uint64_t flat(int row) const { return t0 + (uint64_t)(row * kRow) + lane * kVec; }
     __device__ __forceinline__ uint64_t msg(int row) const { return mb + (uint64_t)(row * kRow) + lane * kVec; }
+    __device__ __forceinline__ uint64_t state(int row) const { return s0 + (uint64_t)(row * kRow) + lane * kVec; }
 
     __device__ __forceinline__ void ld_f32(const float* p, int n, float (&v)[kVec]) const
     {
@@ -456,10 +461,10 @@ struct GuardedIO {
         }
     }
 
-    __device__ __forceinline__ void load_g(int row, float (&v)[kVec]) const { ld_f32(a.g + flat(row), valid(row), v); }
-    __device__ __forceinline__ void load_mom(int row, float (&v)[kVec]) const { ld_f32(a.mom + flat(row), valid(row), v); }
-    __device__ __forceinline__ void store_g(int row, const float (&v)[kVec]) const { st_f32(a.g + flat(row), valid(row), v); }
-    __device__ __forceinline__ void store_mom(int row, const float (&v)[kVec]) const { st_f32(a.mom + flat(row), valid(row), v); }
+    __device__ __forceinline__ void load_g(int row, float (&v)[kVec]) const { ld_f32(a.g + state(row), valid(row), v); }
+    __device__ __forceinline__ void load_mom(int row, float (&v)[kVec]) const { ld_f32(a.mom + state(row), valid(row), v); }
+    __device__ __forceinline__ void store_g(int row, const float (&v)[kVec]) const { st_f32(a.g + state(row), valid(row), v); }
+    __device__ __forceinline__ void store_mom(int row, const float (&v)[kVec]) const { st_f32(a.mom + state(row), valid(row), v); }
     __device__ __forceinline__ void load_ws(uint32_t m, int row, uint32_t (&u)[2]) const { ld_bf16(a.w_send[m] + flat(row), valid(row), u); }
     __device__ __forceinline__ void load_wn(uint32_t m, int row, uint32_t (&u)[2]) const { ld_bf16(a.w_now[m] + flat(row), valid(row), u); }
     __device__ __forceinline__ void store_wn(uint32_t m, int row, const uint32_t (&u)[2]) const { st_bf16(a.w_now[m] + flat(row), valid(row), u); }
@@ -689,10 +694,12 @@ void sdl_kernel(const Args a)
     const uint64_t run_n = a.runs[r].numel;
     const uint64_t tile = (uint64_t)(wg - a.runs[r].first_wg) * kGroup;   // first element of the tile in the run
     if (a.runs[r].vec && run_n - tile >= (uint64_t)kGroup) {
-        const TileIO io{a, run_off + tile, a.runs[r].msg + tile, threadIdx.x, a.runs[r].sidx};
+        const TileIO io{a, run_off + tile, a.runs[r].msg + tile, threadIdx.x, a.runs[r].sidx,
+                        a.staged ? a.runs[r].soff + tile : run_off + tile};
         process<MODE, FMT, MT, ALIASED, EMIT>(a, io);
     } else {
-        const GuardedIO io{a, run_off + tile, tile, a.runs[r].msg + tile, run_n, threadIdx.x, a.runs[r].sidx};
+        const GuardedIO io{a, run_off + tile, tile, a.runs[r].msg + tile, run_n, threadIdx.x, a.runs[r].sidx,
+                           a.staged ? a.runs[r].soff + tile : run_off + tile};
         process<MODE, FMT, 0, ALIASED, EMIT>(a, io);
     }
 }
@@ -809,11 +816,11 @@ struct RunBuilder {
     uint64_t n_wg = 0;
     explicit RunBuilder(Args* args) : a(args) { a->n_runs = 0; }
     bool full() const { return a->n_runs == kMaxRuns; }
-    void add(uint64_t offset, uint64_t numel, bool vec, uint64_t msg = 0, uint32_t sidx = 0)
+    void add(uint64_t offset, uint64_t numel, bool vec, uint64_t msg = 0, uint32_t sidx = 0, uint64_t soff = 0)
     {
         Run& r = a->runs[a->n_runs++];
-        r.offset = offset; r.numel = numel; r.msg = msg; r.first_wg = (uint32_t)n_wg; r.vec = vec ? 1u : 0u;
-        r.sidx = sidx; r.pad_ = 0;
+        r.offset = offset; r.numel = numel; r.msg = msg; r.soff = soff; r.first_wg = (uint32_t)n_wg;
+        r.vec = vec ? 1u : 0u; r.sidx = sidx; r.pad_ = 0;
         n_wg += (numel + kGroup - 1) / kGroup;
     }
 };
@@ -971,17 +978,30 @@ static int launch_fragment(Args& a, const sdl_plan_t* plan, uint32_t p, bool vec
     // the pieces that are processed: joined runs, or, for the whole-span scale, the spans
     // themselves (one scale word per parameter group)
     const sdl_span_t* runs = nullptr;
-    uint32_t n_runs = 0;
-    int rc = is_span_scaled(fmt) && MODE != kMerge ? sdl_plan_fragment_spans(plan, p, &runs, &n_runs)
-                                                   : sdl_plan_fragment_runs(plan, p, &runs, &n_runs);
+    const sdl_span_t* pieces = nullptr;
+    uint32_t n_runs = 0, n_pieces = 0;
+    int rc = sdl_plan_fragment_runs(plan, p, &runs, &n_runs);
     if (rc != SDL_OK) return rc;
-    uint64_t msg = 0;
-    for (uint32_t first = 0; first < n_runs; first += kMaxRuns) {
+    if (is_span_scaled(fmt) && MODE != kMerge) rc = sdl_plan_fragment_spans(plan, p, &pieces, &n_pieces);
+    else { pieces = runs; n_pieces = n_runs; }
+    if (rc != SDL_OK) return rc;
+    // staged g / mom hold the fragment's runs back to back, each padded to whole tiles
+    uint64_t msg = 0, run_start = 0;
+    uint32_t run_i = 0;
+    for (uint32_t first = 0; first < n_pieces; first += kMaxRuns) {
         RunBuilder rb(&a);
-        for (uint32_t i = first; i < n_runs && i < first + kMaxRuns; ++i) {
-            // a run keeps the 16-byte alignment of the bases when it starts on a multiple of 8 elements
-            rb.add(runs[i].offset, runs[i].numel, vec && (runs[i].offset % 8 == 0), msg, i);
-            msg += (runs[i].numel + kGroup - 1) / kGroup * kGroup;
+        for (uint32_t i = first; i < n_pieces && i < first + kMaxRuns; ++i) {
+            if (pieces[i].numel == 0) continue;
+            // the run that contains this piece, and where that run starts in the staged arrays
+            while (run_i < n_runs && pieces[i].offset >= runs[run_i].offset + runs[run_i].numel) {
+                run_start += (runs[run_i].numel + kGroup - 1) / kGroup * kGroup;
+                ++run_i;
+            }
+            const uint64_t soff = run_i < n_runs ? run_start + (pieces[i].offset - runs[run_i].offset) : 0;
+            // a piece keeps the 16-byte alignment of the bases when it starts on a multiple of 8 elements
+            const bool piece_vec = vec && (pieces[i].offset % 8 == 0) && (!a.staged || soff % 8 == 0);
+            rb.add(pieces[i].offset, pieces[i].numel, piece_vec, msg, i, soff);
+            msg += (pieces[i].numel + kGroup - 1) / kGroup * kGroup;
         }
         if (rb.n_wg > 0x7fffffffull) return SDL_ERR_UNSUPPORTED;
         if (rb.n_wg == 0) continue;
@@ -1009,9 +1029,9 @@ int sdl_plan_message_bytes(const sdl_plan_t* plan, uint32_t p, sdl_format_t fmt,
     return SDL_OK;
 }
 
-int sdl_fragment_outer_step_plan(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
-                                 const void* const* w_send_base, void* const* w_now_base, uint32_t M,
-                                 sdl_format_t fmt, float lr, float mu, float alpha, void* stream)
+static int fused_fragment(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
+                          const void* const* w_send_base, void* const* w_now_base, uint32_t M,
+                          sdl_format_t fmt, float lr, float mu, float alpha, void* stream, bool staged)
 {
     if (!plan || p >= sdl_plan_num_fragments(plan)) return SDL_ERR_INVALID_ARG;
     // the whole-span scale needs scale words, which this call has no argument for: use the
@@ -1021,12 +1041,13 @@ int sdl_fragment_outer_step_plan(const sdl_plan_t* plan, uint32_t p, float* g_ba
     bool vec = false;
     int rc = fill_fused_args(a, g_base, mom_base, w_send_base, w_now_base, M, fmt, lr, mu, alpha, &vec);
     if (rc != SDL_OK) return rc;
+    a.staged = staged ? 1u : 0u;
     return launch_fragment<kFused>(a, plan, p, vec, fmt, stream);
 }
 
-int sdl_quantize_outer_grad_plan(const sdl_plan_t* plan, uint32_t p, const float* g_base,
-                                 const void* const* w_send_base, uint32_t M, sdl_format_t fmt,
-                                 void* const* codes, void* const* scales, void* stream)
+static int quantize_fragment(const sdl_plan_t* plan, uint32_t p, const float* g_base,
+                             const void* const* w_send_base, uint32_t M, sdl_format_t fmt,
+                             void* const* codes, void* const* scales, void* stream, bool staged)
 {
     if (!plan || p >= sdl_plan_num_fragments(plan)) return SDL_ERR_INVALID_ARG;
     if (!valid_format(fmt) || M == 0 || M > SDL_MAX_WORKERS) return SDL_ERR_INVALID_ARG;
@@ -1047,12 +1068,13 @@ int sdl_quantize_outer_grad_plan(const sdl_plan_t* plan, uint32_t p, const float
         a.codes[m] = static_cast<uint8_t*>(codes[m]);
         a.scales[m] = scaled ? static_cast<uint8_t*>(scales[m]) : nullptr;
     }
+    a.staged = staged ? 1u : 0u;
     return launch_fragment<kQuantize>(a, plan, p, vec, fmt, stream);
 }
 
-int sdl_dequant_reduce_nesterov_plan(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
-                                     const void* const* codes, const void* const* scales, uint32_t M,
-                                     sdl_format_t fmt, float lr, float mu, void* stream)
+static int reduce_fragment(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
+                           const void* const* codes, const void* const* scales, uint32_t M,
+                           sdl_format_t fmt, float lr, float mu, void* stream, bool staged)
 {
     if (!plan || p >= sdl_plan_num_fragments(plan)) return SDL_ERR_INVALID_ARG;
     if (!valid_format(fmt) || M == 0 || M > SDL_MAX_WORKERS) return SDL_ERR_INVALID_ARG;
@@ -1071,11 +1093,12 @@ int sdl_dequant_reduce_nesterov_plan(const sdl_plan_t* plan, uint32_t p, float* 
         a.codes[m] = static_cast<uint8_t*>(const_cast<void*>(codes[m]));
         a.scales[m] = scaled ? static_cast<uint8_t*>(const_cast<void*>(scales[m])) : nullptr;
     }
+    a.staged = staged ? 1u : 0u;
     return launch_fragment<kReduce>(a, plan, p, vec, fmt, stream);
 }
 
-int sdl_merge_overlap_plan(const sdl_plan_t* plan, uint32_t p, const float* g_new_base, void* const* w_now_base,
-                           uint32_t M, float alpha, void* stream)
+static int merge_fragment(const sdl_plan_t* plan, uint32_t p, const float* g_new_base, void* const* w_now_base,
+                          uint32_t M, float alpha, void* stream, bool staged)
 {
     if (!plan || p >= sdl_plan_num_fragments(plan)) return SDL_ERR_INVALID_ARG;
     if (M == 0 || M > SDL_MAX_WORKERS || !g_new_base || !w_now_base) return SDL_ERR_INVALID_ARG;
@@ -1090,7 +1113,66 @@ int sdl_merge_overlap_plan(const sdl_plan_t* plan, uint32_t p, const float* g_ne
         vec = vec && aligned(w_now_base[m], 16);
         a.w_now[m] = static_cast<uint16_t*>(w_now_base[m]);
     }
+    a.staged = staged ? 1u : 0u;
     return launch_fragment<kMerge>(a, plan, p, vec, SDL_FMT_FP32, stream);
+}
+
+
+int sdl_fragment_outer_step_plan(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
+                                 const void* const* w_send_base, void* const* w_now_base, uint32_t M,
+                                 sdl_format_t fmt, float lr, float mu, float alpha, void* stream)
+{
+    return fused_fragment(plan, p, g_base, mom_base, w_send_base, w_now_base, M, fmt, lr, mu, alpha, stream, false);
+}
+int sdl_quantize_outer_grad_plan(const sdl_plan_t* plan, uint32_t p, const float* g_base,
+                                 const void* const* w_send_base, uint32_t M, sdl_format_t fmt,
+                                 void* const* codes, void* const* scales, void* stream)
+{
+    return quantize_fragment(plan, p, g_base, w_send_base, M, fmt, codes, scales, stream, false);
+}
+int sdl_dequant_reduce_nesterov_plan(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
+                                     const void* const* codes, const void* const* scales, uint32_t M,
+                                     sdl_format_t fmt, float lr, float mu, void* stream)
+{
+    return reduce_fragment(plan, p, g_base, mom_base, codes, scales, M, fmt, lr, mu, stream, false);
+}
+int sdl_merge_overlap_plan(const sdl_plan_t* plan, uint32_t p, const float* g_new_base, void* const* w_now_base,
+                           uint32_t M, float alpha, void* stream)
+{
+    return merge_fragment(plan, p, g_new_base, w_now_base, M, alpha, stream, false);
+}
+
+uint64_t sdl_plan_staged_numel(const sdl_plan_t* plan, uint32_t p)
+{
+    const sdl_span_t* runs = nullptr;
+    uint32_t n_runs = 0;
+    if (sdl_plan_fragment_runs(plan, p, &runs, &n_runs) != SDL_OK) return 0;
+    uint64_t padded = 0;
+    for (uint32_t i = 0; i < n_runs; ++i) padded += (runs[i].numel + kGroup - 1) / kGroup * kGroup;
+    return padded;
+}
+int sdl_fragment_outer_step_staged(const sdl_plan_t* plan, uint32_t p, float* g_frag, float* mom_frag,
+                                   const void* const* w_send_base, void* const* w_now_base, uint32_t M,
+                                   sdl_format_t fmt, float lr, float mu, float alpha, void* stream)
+{
+    return fused_fragment(plan, p, g_frag, mom_frag, w_send_base, w_now_base, M, fmt, lr, mu, alpha, stream, true);
+}
+int sdl_quantize_outer_grad_staged(const sdl_plan_t* plan, uint32_t p, const float* g_frag,
+                                   const void* const* w_send_base, uint32_t M, sdl_format_t fmt,
+                                   void* const* codes, void* const* scales, void* stream)
+{
+    return quantize_fragment(plan, p, g_frag, w_send_base, M, fmt, codes, scales, stream, true);
+}
+int sdl_dequant_reduce_nesterov_staged(const sdl_plan_t* plan, uint32_t p, float* g_frag, float* mom_frag,
+                                       const void* const* codes, const void* const* scales, uint32_t M,
+                                       sdl_format_t fmt, float lr, float mu, void* stream)
+{
+    return reduce_fragment(plan, p, g_frag, mom_frag, codes, scales, M, fmt, lr, mu, stream, true);
+}
+int sdl_merge_overlap_staged(const sdl_plan_t* plan, uint32_t p, const float* g_new_frag, void* const* w_now_base,
+                             uint32_t M, float alpha, void* stream)
+{
+    return merge_fragment(plan, p, g_new_frag, w_now_base, M, alpha, stream, true);
 }
 
 int sdl_copy_bytes(void* dst, const void* src, uint64_t nbytes, void* stream)

@@ -103,3 +103,59 @@ def test_fragment_level_calls_match_span_level_calls():
     assert torch.equal(g, g2) and torch.equal(mom, mom2)
     for a, b in zip(w_now, wn2):
         assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+@pytest.mark.parametrize("taus,P,fmt,n_slots,lookahead", [
+    ((1, 1), 3, sdl.FMT_E3M0, 3, 1),          # the paper's setting, everything prefetched one step ahead
+    ((0, 0), 3, sdl.FMT_E3M0, 1, 0),          # no overlap, a single slot, fetched on demand
+    ((5, 5, 5, 5), 4, sdl.FMT_E3M0, 4, 2),    # several fragments in flight at once
+    ((1, 4), 2, sdl.FMT_E4M3, 2, 3),
+])
+def test_engine_with_outer_state_in_host_memory(taus, P, fmt, n_slots, lookahead):
+    """Section 2.5: outer parameters and momentum live in (pinned) host memory; fragments are
+    staged through a small pool of device slots on a copy stream.  Same walk, same result."""
+    H, T, M = 12, 3 * 12 + 9, len(taus)
+    lr, mu, alpha = 0.7, 0.9, 0.5
+    numel, block, L = _small_model()
+    plan = sdl.sdl_fragment_plan(numel, block, L, P, sdl.PATTERN_STRIDED, H, min(taus))
+    ref_plan = oracle.fragment_plan(numel, block, L, P, sdl.PATTERN_STRIDED, H, min(taus))
+    total = plan.total_numel
+    g, mom, w, _ = workloads.make_span(total, M, tau=0, delta="normal", device=DEV)
+    ref = oracle.RefEngine(ref_plan, taus, fmt, lr, mu, alpha, host_f32(g), host_f32(mom), [host_bits(x) for x in w])
+    g_host = g.cpu().pin_memory()
+    mom_host = mom.cpu().pin_memory()
+    del g, mom                                     # no flat device copy of the outer state exists
+    pool = sdl.sdl_offload_create(plan, n_slots)
+    assert pool.slot_numel == max(sdl.sdl_plan_staged_numel(plan, p) for p in range(P))
+    slot_g = [torch.full((pool.slot_numel,), float("nan"), device=DEV) for _ in range(n_slots)]
+    slot_mom = [torch.full((pool.slot_numel,), float("nan"), device=DEV) for _ in range(n_slots)]
+    sdl.sdl_offload_bind(pool, g_host, mom_host, slot_g, slot_mom)
+    eng = sdl.sdl_engine_create(plan, H, taus, fmt, lr, mu, alpha)
+    codes, scales = [], []
+    for p in range(P):
+        cb, sb = sdl.sdl_plan_message_bytes(plan, p, fmt)
+        for m in range(M):
+            codes.append(torch.zeros(max(cb, 16), dtype=torch.uint8, device=DEV))
+            scales.append(torch.zeros(max(sb, 16), dtype=torch.uint8, device=DEV))
+    copy_stream = torch.cuda.Stream()
+    sdl.sdl_engine_bind_offload(eng, pool, w, codes, scales, copy_stream=copy_stream, lookahead=lookahead)
+    gen = torch.Generator(DEV).manual_seed(7)
+    prefetched = 0
+    for t in range(1, T + 1):
+        for m in range(M):
+            noise = torch.randn(total, device=DEV, generator=gen) * 3e-4
+            w[m].copy_((w[m].float() + noise).bfloat16())
+            hn = torch.from_numpy(ref.w[m].view(np.int16)).view(torch.bfloat16).float() + noise.cpu()
+            ref.w[m][:] = host_bits(hn.bfloat16())
+        due_next = sdl.sdl_plan_events(plan, t + 1)[0] if lookahead else []
+        assert sdl.sdl_engine_step(eng, t) == ref.step(t)
+        prefetched += sum(sdl.sdl_offload_resident(pool, p) for p in due_next)
+    if lookahead:
+        assert prefetched > 0
+    sdl.sdl_offload_flush(pool, copy_stream)
+    copy_stream.synchronize()
+    torch.cuda.synchronize()
+    assert_f32_close(g_host.numpy(), ref.g, "offloaded g")
+    assert_f32_close(mom_host.numpy(), ref.mom, "offloaded mom")
+    for m in range(M):
+        assert_bf16_within_ulp(host_bits(w[m]), ref.w[m], f"offloaded w[{m}]")
