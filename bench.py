@@ -94,6 +94,8 @@ def main() -> int:
     ap.add_argument("--workers", type=int, default=None, help="override M")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the unfused / copy side measurements")
+    ap.add_argument("--offload", action="store_true",
+                    help="also time the fragment step with g / mom staged from pinned host memory")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the M workers are M replicas resident in one "
@@ -161,6 +163,8 @@ def main() -> int:
     }
     if not args.no_extras:
         out["extras"] = extras(st, fmt, wl, M, torch, sdl, args)
+    if args.offload:
+        out["offload"] = offload_timing(st, frag, fmt, wl, M, torch, sdl, args)
     print(json.dumps(out))
     return 0
 
@@ -212,6 +216,40 @@ def extras(st, fmt, wl, M, torch, sdl, args):
     dst = torch.empty_like(src)
     t = time_gpu(torch, lambda: sdl.sdl_copy_bytes(dst, src, nbytes), steps, warm)
     res["copy_kernel"] = {"ms": t, "GB/s": 2 * nbytes / t / 1e6, "bytes": nbytes}
+    return res
+
+
+def offload_timing(st, frag, fmt, wl, M, torch, sdl, args):
+    """Outer parameters and momentum in pinned host memory (Section 2.5 of the paper): copy-in of the
+    fragment, staged fused step, write-back -- each timed alone, then the whole round trip."""
+    g_host = st.g.cpu().pin_memory()
+    mom_host = st.mom.cpu().pin_memory()
+    pool = sdl.sdl_offload_create(st.plan, 1)
+    slot_g = [torch.empty(pool.slot_numel, dtype=torch.float32, device="cuda")]
+    slot_mom = [torch.empty(pool.slot_numel, dtype=torch.float32, device="cuda")]
+    sdl.sdl_offload_bind(pool, g_host, mom_host, slot_g, slot_mom)
+    copy = torch.cuda.Stream()
+    res = {"state_bytes": 8 * st.n}
+    t_in, t_step, t_out = [], [], []
+    for _ in range(max(3, args.steps // 10)):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        sdl.sdl_offload_prefetch(pool, frag, copy)
+        copy.synchronize()
+        t1 = time.perf_counter()
+        sdl.sdl_offload_acquire(pool, frag, copy)
+        sdl.sdl_fragment_outer_step_staged(st.plan, frag, slot_g[0], slot_mom[0], st.w_send, st.w_now, fmt, wl.lr,
+                                           wl.mu, wl.alpha)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        sdl.sdl_offload_release(pool, frag, copy)
+        copy.synchronize()
+        t3 = time.perf_counter()
+        t_in.append(t1 - t0), t_step.append(t2 - t1), t_out.append(t3 - t2)
+    for name, ts in (("copy_in", t_in), ("staged_step", t_step), ("write_back", t_out)):
+        ms = 1e3 * sorted(ts)[len(ts) // 2]
+        res[name] = {"ms": ms, "GB/s": (8 * st.n if name != "staged_step" else
+                                        algorithmic_bytes_per_param(M, wl.tau) * st.n) / ms / 1e6}
     return res
 
 
