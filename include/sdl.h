@@ -190,6 +190,14 @@ int sdl_dequant_reduce_nesterov(float* g, float* mom, const void* const* codes,
 int sdl_merge_overlap(const float* g_new, void* const* w_now, uint32_t M, uint64_t n, float alpha,
                       void* stream);
 
+/* Receive side in one pass: sdl_dequant_reduce_nesterov followed by sdl_merge_overlap of all
+ * M replicas, without re-reading the new global parameters (16 + 4M + M*c bytes per parameter
+ * instead of 20 + 4M + M*c).  Use it when every worker merges at the step the mean is taken
+ * (one common delay tau); results are identical to the two separate calls. */
+int sdl_receive_outer_step(float* g, float* mom, const void* const* codes, const void* const* scales,
+                           void* const* w_now, uint32_t M, uint64_t n, sdl_format_t fmt, float lr, float mu,
+                           float alpha, void* stream);
+
 /* Fused outer step of one span: the three calls above in a single pass over memory,
  * with the messages kept in registers.  g, mom and w_now[m] are updated in place;
  * w_send[m] (the replica as it was at the send step) is only read and may be the same
@@ -226,6 +234,9 @@ int sdl_dequant_reduce_nesterov_plan(const sdl_plan_t* plan, uint32_t p, float* 
                                      sdl_format_t fmt, float lr, float mu, void* stream);
 int sdl_merge_overlap_plan(const sdl_plan_t* plan, uint32_t p, const float* g_new_base, void* const* w_now_base,
                            uint32_t M, float alpha, void* stream);
+int sdl_receive_outer_step_plan(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
+                                const void* const* codes, const void* const* scales, void* const* w_now_base,
+                                uint32_t M, sdl_format_t fmt, float lr, float mu, float alpha, void* stream);
 
 /* ------------------------------------------------------------------ schedule driver
  *
@@ -235,7 +246,8 @@ int sdl_merge_overlap_plan(const sdl_plan_t* plan, uint32_t p, const float* g_ne
  *   - for every fragment that sends at t (t = t_p + k*H): sdl_quantize_outer_grad_plan into
  *     that fragment's message buffers (the exchange between workers would happen here);
  *   - tau steps later: sdl_dequant_reduce_nesterov_plan, then sdl_merge_overlap_plan into
- *     the replicas as they are then (Section 2.3);
+ *     the replicas as they are then (Section 2.3) -- as the single pass
+ *     sdl_receive_outer_step_plan when all workers share one delay;
  *   - with tau = 0 for every worker: sdl_fragment_outer_step_plan at the send step.
  * tau_m[m] < H is worker m's delay (Section 3.3.2: workers may receive the same update at
  * different steps); the mean and the Nesterov update happen once, at the smallest delay,
@@ -275,6 +287,9 @@ int sdl_dequant_reduce_nesterov_staged(const sdl_plan_t* plan, uint32_t p, float
                                        sdl_format_t fmt, float lr, float mu, void* stream);
 int sdl_merge_overlap_staged(const sdl_plan_t* plan, uint32_t p, const float* g_new_frag, void* const* w_now_base,
                              uint32_t M, float alpha, void* stream);
+int sdl_receive_outer_step_staged(const sdl_plan_t* plan, uint32_t p, float* g_frag, float* mom_frag,
+                                  const void* const* codes, const void* const* scales, void* const* w_now_base,
+                                  uint32_t M, sdl_format_t fmt, float lr, float mu, float alpha, void* stream);
 
 /* The staging pool.  g_host / mom_host: the whole model's outer parameters and momentum in
  * host memory (flat layout; pinned memory makes the copies asynchronous).  slot_g / slot_mom:

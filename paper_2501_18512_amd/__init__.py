@@ -82,6 +82,9 @@ def _load() -> ctypes.CDLL:
     lib.sdl_engine_destroy.restype = None
     lib.sdl_engine_bind.argtypes = [vp, vp, vp, pp, pp, pp]
     lib.sdl_engine_step.argtypes = [vp, u64, vp, ctypes.POINTER(u32), ctypes.POINTER(u32)]
+    lib.sdl_receive_outer_step.argtypes = [vp, vp, pp, pp, pp, u32, u64, ctypes.c_int, f32, f32, f32, vp]
+    lib.sdl_receive_outer_step_plan.argtypes = [vp, u32, vp, vp, pp, pp, pp, u32, ctypes.c_int, f32, f32, f32, vp]
+    lib.sdl_receive_outer_step_staged.argtypes = lib.sdl_receive_outer_step_plan.argtypes
     lib.sdl_plan_staged_numel.argtypes = [vp, u32]
     lib.sdl_plan_staged_numel.restype = u64
     lib.sdl_fragment_outer_step_staged.argtypes = lib.sdl_fragment_outer_step_plan.argtypes
@@ -268,6 +271,24 @@ def sdl_merge_overlap(g_new, w_now, n: int, alpha: float, stream=None):
     _require_device(g_new, *w_now)
     _check(_lib.sdl_merge_overlap(_ptr(g_new), _ptr_array(w_now), len(w_now), n, alpha,
                                   _stream(stream)), "sdl_merge_overlap")
+
+
+def sdl_receive_outer_step(g, mom, codes, scales, w_now, n: int, fmt: int, lr: float, mu: float, alpha: float,
+                           stream=None):
+    _require_device(g, mom, *codes, *(scales or []), *w_now)
+    if len(codes) != len(w_now):
+        raise SdlError(-1, "sdl_receive_outer_step")
+    _check(_lib.sdl_receive_outer_step(_ptr(g), _ptr(mom), _ptr_array(codes), _ptr_array(scales),
+                                       _ptr_array(w_now), len(w_now), n, fmt, lr, mu, alpha, _stream(stream)),
+           "sdl_receive_outer_step")
+
+
+def sdl_receive_outer_step_plan(plan: "Plan", p: int, g_base, mom_base, codes, scales, w_now_base, fmt: int,
+                                lr: float, mu: float, alpha: float, stream=None):
+    _require_device(g_base, mom_base, *codes, *(scales or []), *w_now_base)
+    _check(_lib.sdl_receive_outer_step_plan(plan._h, p, _ptr(g_base), _ptr(mom_base), _ptr_array(codes),
+                                            _ptr_array(scales), _ptr_array(w_now_base), len(w_now_base), fmt, lr,
+                                            mu, alpha, _stream(stream)), "sdl_receive_outer_step_plan")
 
 
 def sdl_fragment_outer_step(g, mom, w_send, w_now, n: int, fmt: int, lr: float, mu: float,

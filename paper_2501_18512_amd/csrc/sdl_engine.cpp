@@ -159,6 +159,17 @@ int sdl_engine_step(sdl_engine_t* e, uint64_t t, void* stream, uint32_t* n_sent,
         // ---- receive side of the message in flight
         if (e->sent_at[p] != 0) {
             const uint64_t ts = e->sent_at[p];
+            if (!e->reduced[p] && t == ts + e->delay_min && e->delay_min == e->delay_max) {
+                // one common delay: mean, Nesterov and the merge of every replica in a single pass
+                int rc = staged ? sdl_receive_outer_step_staged(e->plan, p, g, mom, codes, scales, e->w.data(), M,
+                                                                e->fmt, e->lr, e->mu, e->alpha, stream)
+                                : sdl_receive_outer_step_plan(e->plan, p, g, mom, codes, scales, e->w.data(), M,
+                                                              e->fmt, e->lr, e->mu, e->alpha, stream);
+                if (rc != SDL_OK) return rc;
+                e->reduced[p] = 1;
+                for (uint32_t m = 0; m < M; ++m) e->merged[(size_t)p * M + m] = 1;
+                ++received;
+            }
             if (!e->reduced[p] && t == ts + e->delay_min) {
                 int rc = staged ? sdl_dequant_reduce_nesterov_staged(e->plan, p, g, mom, codes, scales, M, e->fmt,
                                                                      e->lr, e->mu, stream)

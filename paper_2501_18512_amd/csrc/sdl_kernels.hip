@@ -37,7 +37,7 @@ constexpr int kRow = kVec * kWave;            // parameters per row (256)
 constexpr int kGroup = kRow * kRows;          // parameters per workgroup tile (512)
 constexpr int kMaxRuns = 16;                  // runs per launch
 
-enum Mode { kQuantize = 0, kReduce = 1, kMerge = 2, kFused = 3, kAbsmax = 4 };
+enum Mode { kQuantize = 0, kReduce = 1, kMerge = 2, kFused = 3, kAbsmax = 4, kReceive = 5 };   // kReceive = kReduce + kMerge
 
 constexpr bool is_e3m0(int f) { return f == SDL_FMT_E3M0 || f >= SDL_FMT_E3M0_B64; }
 constexpr bool is_scaled(int f) { return f == SDL_FMT_E4M3 || is_e3m0(f); }
@@ -550,7 +550,7 @@ __device__ __forceinline__ void process(const Args& a, const IO& io)
 #pragma unroll
     for (int r = 0; r < kRows; ++r) {
         io.load_g(r, g[r]);
-        if constexpr (MODE == kReduce || MODE == kFused) io.load_mom(r, mom[r]);
+        if constexpr (MODE == kReduce || MODE == kFused || MODE == kReceive) io.load_mom(r, mom[r]);
     }
     if constexpr (MT > 0) {
         if constexpr (MODE == kQuantize || MODE == kFused || MODE == kAbsmax) {
@@ -559,7 +559,7 @@ __device__ __forceinline__ void process(const Args& a, const IO& io)
 #pragma unroll
                 for (int r = 0; r < kRows; ++r) io.load_ws(m, r, ws[m][r]);
         }
-        if constexpr (MODE == kMerge) {
+        if constexpr (MODE == kMerge || MODE == kReceive) {
 #pragma unroll
             for (int m = 0; m < MT; ++m)
 #pragma unroll
@@ -608,7 +608,7 @@ __device__ __forceinline__ void process(const Args& a, const IO& io)
 #pragma unroll
             for (int r = 0; r < kRows; ++r) {
                 float dq[kVec];
-                if constexpr (MODE == kReduce) {
+                if constexpr (MODE == kReduce || MODE == kReceive) {
                     io.template load_message<FMT>(m, r, dq);
                 } else {
                     if constexpr (MT == 0) io.load_ws(m, r, ws[0][r]);
@@ -633,7 +633,7 @@ __device__ __forceinline__ void process(const Args& a, const IO& io)
     }
 
     // ---- mean and Nesterov outer step
-    if constexpr (MODE == kReduce || MODE == kFused) {
+    if constexpr (MODE == kReduce || MODE == kFused || MODE == kReceive) {
         const float fm = (float)M;
 #pragma unroll
         for (int r = 0; r < kRows; ++r) {
@@ -651,7 +651,7 @@ __device__ __forceinline__ void process(const Args& a, const IO& io)
     }
 
     // ---- alpha-merge into every replica
-    if constexpr (MODE == kMerge || MODE == kFused) {
+    if constexpr (MODE == kMerge || MODE == kFused || MODE == kReceive) {
 #pragma unroll
         for (uint32_t m = 0; m < M; ++m) {
             const int mi = MT > 0 ? (int)m : 0;
@@ -745,13 +745,15 @@ size_t code_bytes_at(sdl_format_t fmt, uint64_t elem)
 // streaming kernel: enough loads in flight, not so many that the access window in each
 // array grows and DRAM page locality is lost.  Measured on MI355X: the fused kernel with
 // a compile-time replica count is fastest at 8 wavefronts per CU (12 when w_send aliases
-// w_now); the other kernels want every wavefront they can get.
+// w_now), the one-pass receive kernel at 12; the other kernels want every wavefront they
+// can get.
 // SDL_TUNE_LDS_BYTES in the environment overrides the choice (tuning aid).
 uint32_t lds_cap_bytes(int mode, uint32_t mt, bool aliased)
 {
     static const int env = [] { const char* e = std::getenv("SDL_TUNE_LDS_BYTES"); return e ? std::atoi(e) : -1; }();
     if (env >= 0) return (uint32_t)env;
     if (mode == kFused && mt > 0) return aliased ? 13653u : 20480u;
+    if (mode == kReceive && mt > 0) return 13653u;
     return 0u;
 }
 
@@ -888,6 +890,42 @@ int sdl_dequant_reduce_nesterov(float* g, float* mom, const void* const* codes,
         a.scales[m] = scaled ? static_cast<uint8_t*>(const_cast<void*>(scales[m])) : nullptr;
     }
     return run_single_span<kReduce>(a, n, fmt, vec, stream);
+}
+
+// Argument marshalling shared by the receive-side calls that also merge.
+static int fill_receive_args(Args& a, float* g, float* mom, const void* const* codes, const void* const* scales,
+                             void* const* w_now, uint32_t M, sdl_format_t fmt, float lr, float mu, float alpha,
+                             bool* vec)
+{
+    if (!valid_format(fmt) || M == 0 || M > SDL_MAX_WORKERS) return SDL_ERR_INVALID_ARG;
+    const bool scaled = is_scaled(fmt);
+    if (!g || !mom || !codes || !w_now || (scaled && !scales)) return SDL_ERR_INVALID_ARG;
+    if (!aligned(g, 4) || !aligned(mom, 4)) return SDL_ERR_ALIGNMENT;
+    std::memset(&a, 0, sizeof(a));
+    a.g = g; a.mom = mom; a.M = M; a.lr = lr; a.mu = mu; a.alpha = alpha; a.one_minus_alpha = 1.0f - alpha;
+    *vec = aligned(g, 16) && aligned(mom, 16);
+    for (uint32_t m = 0; m < M; ++m) {
+        if (!codes[m] || !w_now[m] || (scaled && !scales[m])) return SDL_ERR_INVALID_ARG;
+        if (!aligned(codes[m], code_align(fmt)) || !aligned(w_now[m], 2)) return SDL_ERR_ALIGNMENT;
+        if (scaled && !aligned(scales[m], scale_align(fmt))) return SDL_ERR_ALIGNMENT;
+        *vec = *vec && aligned(codes[m], 16) && aligned(w_now[m], 16);
+        a.codes[m] = static_cast<uint8_t*>(const_cast<void*>(codes[m]));
+        a.scales[m] = scaled ? static_cast<uint8_t*>(const_cast<void*>(scales[m])) : nullptr;
+        a.w_now[m] = static_cast<uint16_t*>(w_now[m]);
+    }
+    return SDL_OK;
+}
+
+int sdl_receive_outer_step(float* g, float* mom, const void* const* codes, const void* const* scales,
+                           void* const* w_now, uint32_t M, uint64_t n, sdl_format_t fmt, float lr, float mu,
+                           float alpha, void* stream)
+{
+    if (n == 0) return (valid_format(fmt) && M >= 1 && M <= SDL_MAX_WORKERS) ? SDL_OK : SDL_ERR_INVALID_ARG;
+    Args a;
+    bool vec = false;
+    int rc = fill_receive_args(a, g, mom, codes, scales, w_now, M, fmt, lr, mu, alpha, &vec);
+    if (rc != SDL_OK) return rc;
+    return run_single_span<kReceive>(a, n, fmt, vec, stream);
 }
 
 int sdl_merge_overlap(const float* g_new, void* const* w_now, uint32_t M, uint64_t n, float alpha,
@@ -1097,6 +1135,19 @@ static int reduce_fragment(const sdl_plan_t* plan, uint32_t p, float* g_base, fl
     return launch_fragment<kReduce>(a, plan, p, vec, fmt, stream);
 }
 
+static int receive_fragment(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
+                            const void* const* codes, const void* const* scales, void* const* w_now_base,
+                            uint32_t M, sdl_format_t fmt, float lr, float mu, float alpha, void* stream, bool staged)
+{
+    if (!plan || p >= sdl_plan_num_fragments(plan)) return SDL_ERR_INVALID_ARG;
+    Args a;
+    bool vec = false;
+    int rc = fill_receive_args(a, g_base, mom_base, codes, scales, w_now_base, M, fmt, lr, mu, alpha, &vec);
+    if (rc != SDL_OK) return rc;
+    a.staged = staged ? 1u : 0u;
+    return launch_fragment<kReceive>(a, plan, p, vec, fmt, stream);
+}
+
 static int merge_fragment(const sdl_plan_t* plan, uint32_t p, const float* g_new_base, void* const* w_now_base,
                           uint32_t M, float alpha, void* stream, bool staged)
 {
@@ -1140,6 +1191,19 @@ int sdl_merge_overlap_plan(const sdl_plan_t* plan, uint32_t p, const float* g_ne
                            uint32_t M, float alpha, void* stream)
 {
     return merge_fragment(plan, p, g_new_base, w_now_base, M, alpha, stream, false);
+}
+
+int sdl_receive_outer_step_plan(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
+                                const void* const* codes, const void* const* scales, void* const* w_now_base,
+                                uint32_t M, sdl_format_t fmt, float lr, float mu, float alpha, void* stream)
+{
+    return receive_fragment(plan, p, g_base, mom_base, codes, scales, w_now_base, M, fmt, lr, mu, alpha, stream, false);
+}
+int sdl_receive_outer_step_staged(const sdl_plan_t* plan, uint32_t p, float* g_frag, float* mom_frag,
+                                  const void* const* codes, const void* const* scales, void* const* w_now_base,
+                                  uint32_t M, sdl_format_t fmt, float lr, float mu, float alpha, void* stream)
+{
+    return receive_fragment(plan, p, g_frag, mom_frag, codes, scales, w_now_base, M, fmt, lr, mu, alpha, stream, true);
 }
 
 uint64_t sdl_plan_staged_numel(const sdl_plan_t* plan, uint32_t p)

@@ -89,6 +89,30 @@ def test_fused_step(fmt, M, tau):
 
 
 @pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("M", [1, 3, 4, 8])
+def test_receive_outer_step(fmt, M):
+    """Mean + Nesterov + merge of all replicas in one pass, against the oracle's two steps."""
+    for n in SIZES:
+        print(f"receive fmt={fmt} M={M} n={n}", flush=True)
+        g, mom, w_send, w_now = _span(n, M, tau=1, delta="student_t3")
+        mom.copy_(torch.randn(n, device=DEV, generator=torch.Generator(DEV).manual_seed(n + 2)) * 1e-3)
+        ref = HostCopy(g, mom, w_send, w_now)
+        rc, rs = oracle.quantize_outer_grad(ref.g, ref.w_send, fmt)
+        codes, scales = sdl.alloc_exchange(fmt, n, M)
+        for m in range(M):
+            codes[m][:rc[m].size].copy_(torch.from_numpy(rc[m]))
+            scales[m][:rs[m].size].copy_(torch.from_numpy(rs[m]))
+        sdl.sdl_receive_outer_step(g, mom, codes, scales, w_now, n, fmt, LR, MU, 0.5)
+        torch.cuda.synchronize()
+        oracle.dequant_reduce_nesterov(ref.g, ref.mom, rc, rs, fmt, LR, MU)
+        oracle.merge_overlap(ref.g, ref.w_now, 0.5)
+        assert_f32_close(host_f32(g), ref.g, f"g n={n}")
+        assert_f32_close(host_f32(mom), ref.mom, f"mom n={n}")
+        for m in range(M):
+            assert_bf16_within_ulp(host_bits(w_now[m]), ref.w_now[m], f"w_now[{m}] n={n}")
+
+
+@pytest.mark.parametrize("fmt", FMTS)
 def test_fused_equals_three_calls_on_gpu(fmt):
     n, M = 5 * 2048 + 19, 4
     g, mom, w_send, w_now = _span(n, M, tau=1)
