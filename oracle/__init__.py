@@ -29,23 +29,30 @@ MAX_BLOCK = 128
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "sdl_ref.c")
 _SO = os.path.join(_HERE, "libsdl_ref.so")
+# The mutation test of the pins points this at a deliberately broken build of sdl_ref.c.
+_OVERRIDE = os.environ.get("SDL_ORACLE_LIB")
 _lib = None
+
+
+def compile_source(src: str, out: str) -> None:
+    cmd = ["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
+           "-Wall", "-Wextra", "-o", out, src, "-lm"]
+    subprocess.run(cmd, check=True)
 
 
 def build(force: bool = False) -> str:
     """Compile sdl_ref.c into libsdl_ref.so next to it (gcc, plain C)."""
+    if _OVERRIDE:
+        return _OVERRIDE
     if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
-               "-Wall", "-Wextra", "-o", _SO, _SRC, "-lm"]
-        subprocess.run(cmd, check=True)
+        compile_source(_SRC, _SO)
     return _SO
 
 
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = ctypes.CDLL(_SO)
+        lib = ctypes.CDLL(build())
         pp = ctypes.POINTER(ctypes.c_void_p)
         lib.sdl_ref_exchange_bytes.restype = ctypes.c_size_t
         lib.sdl_ref_exchange_bytes.argtypes = [ctypes.c_int, ctypes.c_uint64,
