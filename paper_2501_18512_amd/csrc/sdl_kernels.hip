@@ -229,12 +229,18 @@ __device__ __forceinline__ void encode(const float (&d)[kVec], float (&dq)[kVec]
             }
             dq[j] = u2f(sign | f2u(val * b.scale));
             if (want_codes) {
+                // the codes come straight from the rounded bit pattern, not from val, so that a
+                // kernel that only writes messages does not carry the decode arithmetic
                 if constexpr (is_e3m0(FMT)) {
-                    const uint32_t E = val == 0.0f ? 0u : (f2u(val) >> 23) - 124u;
+                    const int e = (int)((yb + 0x3fffffu + ((yb >> 23) & 1u)) >> 23) - 124;
+                    const int ec = e < 1 ? 1 : (e > 7 ? 7 : e);
+                    const uint32_t E = y > 0.125f ? (uint32_t)ec : 0u;
                     packed |= ((sign >> 28) | E) << (4 * j);
                 } else {
-                    const uint32_t mag = val < 0.015625f ? (uint32_t)(val * 512.0f)
-                                                         : (f2u(val) >> 20) - 960u;
+                    const uint32_t rn = ((yb + 0x7ffffu + ((yb >> 20) & 1u)) >> 20) - 960u;
+                    uint32_t mag = y < 0.015625f ? (uint32_t)__builtin_rintf(y * 512.0f) : rn;
+                    mag = mag > 0x7eu ? 0x7eu : mag;
+                    mag = (b.degenerate || !(y == y)) ? 0u : mag;
                     packed |= ((sign >> 24) | mag) << (8 * j);
                 }
             }
