@@ -94,6 +94,8 @@ def main() -> int:
     ap.add_argument("--workers", type=int, default=None, help="override M")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the unfused / copy side measurements")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time the receive side and the fused step over M in {1,2,4,8} x {e3m0,e4m3,bf16}")
     ap.add_argument("--offload", action="store_true",
                     help="also time the fragment step with g / mom staged from pinned host memory")
     args = ap.parse_args()
@@ -163,6 +165,8 @@ def main() -> int:
     }
     if not args.no_extras:
         out["extras"] = extras(st, fmt, wl, M, torch, sdl, args)
+    if args.sweep:
+        out["sweep"] = sweep(st, frag, wl, M, torch, sdl, args)
     if args.offload:
         out["offload"] = offload_timing(st, frag, fmt, wl, M, torch, sdl, args)
     print(json.dumps(out))
@@ -216,6 +220,31 @@ def extras(st, fmt, wl, M, torch, sdl, args):
     dst = torch.empty_like(src)
     t = time_gpu(torch, lambda: sdl.sdl_copy_bytes(dst, src, nbytes), steps, warm)
     res["copy_kernel"] = {"ms": t, "GB/s": 2 * nbytes / t / 1e6, "bytes": nbytes}
+    return res
+
+
+def sweep(st, frag, wl, M, torch, sdl, args):
+    """Bandwidth curve of the stress configuration: replica counts 1, 2, 4, 8 (up to the M that was
+    allocated) and exchange formats E3M0 / E4M3 / BF16, for the receive side alone
+    (sdl_dequant_reduce_nesterov_plan: 16 + M*c bytes per parameter) and for the fused step."""
+    res = {}
+    steps, warm = max(5, args.steps // 5), 2
+    for fmt_name in ("e3m0", "e4m3", "bf16"):
+        f = sdl.FORMATS[fmt_name]
+        cb, sb = sdl.sdl_plan_message_bytes(st.plan, frag, f)
+        codes = [torch.zeros(max(cb, 16), dtype=torch.uint8, device="cuda") for _ in range(M)]
+        scales = [torch.zeros(max(sb, 16), dtype=torch.uint8, device="cuda") for _ in range(M)]
+        sdl.sdl_quantize_outer_grad_plan(st.plan, frag, st.g, st.w_send, f, codes, scales)
+        for m in (1, 2, 4, 8):
+            if m > M:
+                continue
+            t_r = time_gpu(torch, lambda: sdl.sdl_dequant_reduce_nesterov_plan(
+                st.plan, frag, st.g, st.mom, codes[:m], scales[:m], f, wl.lr, wl.mu), steps, warm)
+            t_f = time_gpu(torch, lambda: sdl.sdl_fragment_outer_step_plan(
+                st.plan, frag, st.g, st.mom, st.w_send[:m], st.w_now[:m], f, wl.lr, wl.mu, wl.alpha), steps, warm)
+            res[f"{fmt_name}_M{m}"] = {
+                "reduce_ms": t_r, "reduce_GB/s": (16.0 * st.n + m * (cb + sb)) / t_r / 1e6,
+                "fused_ms": t_f, "fused_GB/s": algorithmic_bytes_per_param(m, wl.tau) * st.n / t_f / 1e6}
     return res
 
 

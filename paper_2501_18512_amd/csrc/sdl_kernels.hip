@@ -1,15 +1,19 @@
 // Device side of the library: the streaming kernels of the fragment outer step for
 // gfx950 (MI355X), and the C entry points that launch them.
 //
-// Work decomposition (all four kernels).  A workgroup is one 64-lane wavefront and owns a
+// One templated kernel serves every call: send side (quantize), receive side (decode + mean +
+// Nesterov, with or without the merge), merge alone, the fused outer step, and the
+// absolute-maximum pre-pass of the whole-span scale.
+//
+// Work decomposition (all modes).  A workgroup is one 64-lane wavefront and owns a
 // tile of 512 consecutive parameters, seen as two rows of 256.  Lane l owns the four
 // parameters [4l, 4l+4) of each row, so
 //   - every memory instruction of the wavefront touches one contiguous piece of an
 //     array (1 KiB of fp32 through 128-bit accesses, 512 B of bf16 through 64-bit
 //     accesses): whole cache lines, nothing strided;
 //   - eight neighbouring lanes own one 32-element scale block, and the block maximum
-//     is three DPP exchanges (two inside the quad, one across the half row); nothing
-//     goes through LDS.
+//     is three DPP exchanges (two inside the quad, one across the half row); wider
+//     blocks add a row mirror and ds_bpermute exchanges.  No LDS storage is used.
 // Full, 16-byte aligned tiles use buffer instructions with non-temporal cache policy
 // (every byte is touched once); ragged tails and unaligned runs use guarded
 // element-wise accesses.  A launch covers up to kMaxRuns contiguous runs of the flat
@@ -86,9 +90,6 @@ struct Args {
 #define SDL_AUX_SCALE 0      // scale bytes: 16 per tile, 8 tiles per cache line -> let L2 combine them
 #endif
 
-#ifndef SDL_SERIALIZE_FROM
-#define SDL_SERIALIZE_FROM 4
-#endif
 #ifndef SDL_WAVES_PER_EU
 #define SDL_WAVES_PER_EU 2   // register budget: at least this many wavefronts per SIMD
 #endif
@@ -632,9 +633,6 @@ __device__ __forceinline__ void process(const Args& a, const IO& io)
 #pragma unroll
                 for (int j = 0; j < kVec; ++j) acc[r][j] = acc[r][j] + dq[j];
             }
-            // finish one replica before the next: keeps the live registers of the wide
-            // variants within the budget of SDL_WAVES_PER_EU
-            if constexpr (MT >= SDL_SERIALIZE_FROM) __builtin_amdgcn_sched_barrier(0);
         }
     }
 

@@ -21,12 +21,12 @@ def test_config_tiny():
     g, mom, w_send, w_now = workloads.make_span(n, wl.M, tau=wl.tau, delta=wl.delta, base_seed=wl.seed,
                                                 device=DEV)
     ref = check_fused_against_oracle(g, mom, w_send, w_now, sdl.FORMATS[wl.fmt], wl.lr, wl.mu, wl.alpha,
-                                     emit=True, what="tiny round 1")
+                                     emit=True, what="tiny, first outer step")
     # second round: the replicas move on, the momentum is no longer zero
     for w in w_now:
         w.copy_((w.float() + torch.randn(n, device=DEV) * 1e-3).bfloat16())
     check_fused_against_oracle(g, mom, w_now, w_now, sdl.FORMATS[wl.fmt], wl.lr, wl.mu, wl.alpha,
-                               emit=True, what="tiny round 2")
+                               emit=True, what="tiny, second outer step")
     assert float(mom.abs().max()) > 0
 
 

@@ -159,3 +159,44 @@ def test_engine_with_outer_state_in_host_memory(taus, P, fmt, n_slots, lookahead
     assert_f32_close(mom_host.numpy(), ref.mom, "offloaded mom")
     for m in range(M):
         assert_bf16_within_ulp(host_bits(w[m]), ref.w[m], f"offloaded w[{m}]")
+
+
+def test_fragment_step_can_be_captured_in_a_graph():
+    """The calls only enqueue kernels (no allocation, no synchronisation, no memset node), so a
+    caller may capture them in a HIP graph.  Three replays, with eager work and synchronisations
+    between them, each checked against the eager result from the same starting state."""
+    wl = workloads.WORKLOADS["tiny"]
+    n, M, fmt = 1 << 18, 2, sdl.FMT_E3M0
+    g, mom, w_send, w_now = workloads.make_span(n, M, tau=1, delta="student_t3", device=DEV)
+    plan = sdl.sdl_fragment_plan([n // 2, n // 2 - 96, 96], [0, 1, 1], 2, 1, sdl.PATTERN_STRIDED, 10, 1)
+    span_scales = sdl.alloc_exchange(sdl.FMT_E3M0_SPAN, n, M)[1]
+    # eager reference: three consecutive steps, state saved after each
+    eg, em, ew = g.clone(), mom.clone(), [x.clone() for x in w_now]
+    want = []
+    for _ in range(3):
+        sdl.sdl_fragment_outer_step_plan(plan, 0, eg, em, w_send, ew, fmt, wl.lr, wl.mu, wl.alpha)
+        sdl.sdl_fragment_outer_step(eg, em, w_send, ew, n, sdl.FMT_E3M0_SPAN, wl.lr, wl.mu, wl.alpha, scales=span_scales)
+        torch.cuda.synchronize()
+        want.append((eg.clone(), em.clone(), [x.clone() for x in ew]))
+    # captured: the same two calls in one graph
+    cg, cm, cw = g.clone(), mom.clone(), [x.clone() for x in w_now]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # warm-up outside the capture
+        sdl.sdl_copy_bytes(cm, cm, 0)
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sdl.sdl_fragment_outer_step_plan(plan, 0, cg, cm, w_send, cw, fmt, wl.lr, wl.mu, wl.alpha)
+        sdl.sdl_fragment_outer_step(cg, cm, w_send, cw, n, sdl.FMT_E3M0_SPAN, wl.lr, wl.mu, wl.alpha, scales=span_scales)
+    # the capture itself does not execute: state still at the start
+    assert torch.equal(cg, g)
+    scratch = torch.zeros(1 << 20, device=DEV)
+    for k in range(3):
+        graph.replay()
+        scratch.add_(1.0).sum().item()                  # eager work and a synchronisation between replays
+        torch.cuda.synchronize()
+        eg_k, em_k, ew_k = want[k]
+        assert torch.equal(cg, eg_k) and torch.equal(cm, em_k), f"replay {k}"
+        for a, b in zip(cw, ew_k):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"replay {k}"
