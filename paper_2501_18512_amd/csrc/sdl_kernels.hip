@@ -207,42 +207,43 @@ __device__ __forceinline__ void encode(const float (&d)[kVec], float (&dq)[kVec]
         const BlockScale b = block_scale_from_exponent<FMT>(amax >> 23);
         sb = b.sb;
         uint32_t packed = 0;
+        if constexpr (FMT == SDL_FMT_E4M3) {
+            // OCP FP8 E4M3 through the conversion instructions of gfx950 (round to nearest even,
+            // subnormals, signed zero); they do not saturate, so clamp to +-448 first
+            float y[kVec];
 #pragma unroll
-        for (int j = 0; j < kVec; ++j) {
-            const float y = __builtin_fabsf(d[j]) * b.inv;     // exact power-of-two scaling
-            const uint32_t yb = f2u(y);
-            const uint32_t sign = f2u(d[j]) & 0x80000000u;
-            float val;
-            if constexpr (is_e3m0(FMT)) {
+            for (int j = 0; j < kVec; ++j) y[j] = __builtin_amdgcn_fmed3f(d[j] * b.inv, 448.0f, -448.0f);
+            packed = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], 0, false);
+            packed = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], (int)packed, true);
+            if (b.sb == 255u) {
+                // a block that holds Inf / NaN keeps only the signs (0 * Inf made NaN codes above)
+                packed = 0;
+#pragma unroll
+                for (int j = 0; j < kVec; ++j) packed |= ((f2u(d[j]) >> 24) & 0x80u) << (8 * j);
+            }
+            const f32x2_t lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)packed, false);
+            const f32x2_t hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)packed, true);
+            dq[0] = lo.x * b.scale; dq[1] = lo.y * b.scale; dq[2] = hi.x * b.scale; dq[3] = hi.y * b.scale;
+        } else {
+#pragma unroll
+            for (int j = 0; j < kVec; ++j) {
+                const float y = __builtin_fabsf(d[j]) * b.inv;     // exact power-of-two scaling
+                const uint32_t yb = f2u(y);
+                const uint32_t sign = f2u(d[j]) & 0x80000000u;
                 // nearest power of two in the linear domain; a tie (mantissa exactly
                 // 1.5) goes to the even exponent code, whose parity is that of the
                 // biased fp32 exponent because the re-bias (124) is even
-                const uint32_t r = (yb + 0x3fffffu + ((yb >> 23) & 1u)) & 0x7f800000u;
-                const float pw = __builtin_amdgcn_fmed3f(u2f(r), 0.25f, 16.0f);
-                val = y > 0.125f ? pw : 0.0f;                  // half of the smallest magnitude
-            } else {
-                // E4M3: 3 mantissa bits above 2^-6, multiples of 2^-9 below, max 448
-                const uint32_t r = (yb + 0x7ffffu + ((yb >> 20) & 1u)) & 0xfff00000u;
-                const float vs = __builtin_rintf(y * 512.0f) * 0.001953125f;
-                val = y < 0.015625f ? vs : u2f(r);
-                val = __builtin_fminf(val, 448.0f);
-                val = b.degenerate ? 0.0f : val;
-            }
-            dq[j] = u2f(sign | f2u(val * b.scale));
-            if (want_codes) {
-                // the codes come straight from the rounded bit pattern, not from val, so that a
-                // kernel that only writes messages does not carry the decode arithmetic
-                if constexpr (is_e3m0(FMT)) {
-                    const int e = (int)((yb + 0x3fffffu + ((yb >> 23) & 1u)) >> 23) - 124;
+                const uint32_t rr = yb + 0x3fffffu + ((yb >> 23) & 1u);
+                const float pw = __builtin_amdgcn_fmed3f(u2f(rr & 0x7f800000u), 0.25f, 16.0f);
+                const float val = y > 0.125f ? pw : 0.0f;          // half of the smallest magnitude
+                dq[j] = u2f(sign | f2u(val * b.scale));
+                if (want_codes) {
+                    // the code comes straight from the rounded bit pattern, not from val, so that a
+                    // kernel that only writes messages does not carry the decode arithmetic
+                    const int e = (int)(rr >> 23) - 124;
                     const int ec = e < 1 ? 1 : (e > 7 ? 7 : e);
                     const uint32_t E = y > 0.125f ? (uint32_t)ec : 0u;
                     packed |= ((sign >> 28) | E) << (4 * j);
-                } else {
-                    const uint32_t rn = ((yb + 0x7ffffu + ((yb >> 20) & 1u)) >> 20) - 960u;
-                    uint32_t mag = y < 0.015625f ? (uint32_t)__builtin_rintf(y * 512.0f) : rn;
-                    mag = mag > 0x7eu ? 0x7eu : mag;
-                    mag = (b.degenerate || !(y == y)) ? 0u : mag;
-                    packed |= ((sign >> 24) | mag) << (8 * j);
                 }
             }
         }
@@ -263,12 +264,20 @@ __device__ __forceinline__ void decode_e3m0(uint32_t c0, float scale, float (&dq
 }
 __device__ __forceinline__ void decode_e4m3(uint32_t c0, float scale, float (&dq)[kVec])
 {
+    // codes 0x7f / 0xff never come out of the encoder; read as a number (480) like every other
+    // code rather than as the NaN the conversion instruction makes of them
+    if (((c0 & 0x7f7f7f7fu) + 0x01010101u) & 0x80808080u) {
 #pragma unroll
-    for (int j = 0; j < kVec; ++j) {
-        const uint32_t byte = (c0 >> (8 * j)) & 255u;
-        const uint32_t mag = byte & 0x7fu;
-        const float val = mag >= 8u ? u2f((mag + 960u) << 20) : (float)mag * 0.001953125f;
-        dq[j] = u2f(((byte & 0x80u) << 24) | f2u(val * scale));
+        for (int j = 0; j < kVec; ++j) {
+            const uint32_t byte = (c0 >> (8 * j)) & 255u;
+            const uint32_t mag = byte & 0x7fu;
+            const float val = mag >= 8u ? u2f((mag + 960u) << 20) : (float)mag * 0.001953125f;
+            dq[j] = u2f(((byte & 0x80u) << 24) | f2u(val * scale));
+        }
+    } else {
+        const f32x2_t lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)c0, false);
+        const f32x2_t hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)c0, true);
+        dq[0] = lo.x * scale; dq[1] = lo.y * scale; dq[2] = hi.x * scale; dq[3] = hi.y * scale;
     }
 }
 

@@ -61,6 +61,36 @@ def test_dequant_reduce_nesterov(fmt, M):
         assert_f32_close(host_f32(mom), hmom, f"mom n={n}")
 
 
+@pytest.mark.parametrize("fmt", [sdl.FMT_E3M0, sdl.FMT_E4M3, sdl.FMT_E3M0_B64, sdl.FMT_E3M0_B128])
+@pytest.mark.parametrize("M", [1, 3])
+def test_receive_side_decodes_every_code_and_scale(fmt, M):
+    """Messages are plain bytes: whatever a peer sends is decoded like the oracle decodes it,
+    including the codes the encoder never produces and the extreme scale bytes."""
+    n = 4 * 2048 + 96
+    rng = np.random.default_rng(1234 + fmt)
+    cb, sb = sdl.sdl_exchange_bytes(fmt, n)
+    rc, rs = [], []
+    for m in range(M):
+        c = rng.integers(0, 256, cb, dtype=np.uint8)
+        c[:256] = np.arange(256, dtype=np.uint8)                 # every byte value at least once
+        s = rng.integers(100, 150, sb, dtype=np.uint8)
+        s[:8] = [0, 1, 2, 127, 253, 254, 255, 126]
+        rc.append(c), rs.append(s)
+    hg = rng.standard_normal(n).astype(np.float32)
+    hmom = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    g, mom = torch.from_numpy(hg).to(DEV), torch.from_numpy(hmom).to(DEV)
+    codes, scales = sdl.alloc_exchange(fmt, n, M)
+    for m in range(M):
+        codes[m][:cb].copy_(torch.from_numpy(rc[m]))
+        scales[m][:sb].copy_(torch.from_numpy(rs[m]))
+    sdl.sdl_dequant_reduce_nesterov(g, mom, codes, scales, n, fmt, LR, MU)
+    torch.cuda.synchronize()
+    oracle.dequant_reduce_nesterov(hg, hmom, rc, rs, fmt, LR, MU)
+    assert np.isnan(hg).any() and np.isfinite(hg).any()
+    assert_f32_close(host_f32(g), hg, "g")
+    assert_f32_close(host_f32(mom), hmom, "mom")
+
+
 @pytest.mark.parametrize("alpha", [0.0, 0.5, 1.0, 0.3])
 @pytest.mark.parametrize("M", [1, 2, 3, 4, 8])
 def test_merge_overlap(alpha, M):
