@@ -68,7 +68,7 @@ class Workload:
     alpha: float
     lr: float
     mu: float
-    delta: str                  # "normal" | "student_t3" | "outliers"
+    delta: str                  # "normal" | "student_t3" | "outliers" | "shared<percent>"
     fmt: str                    # "e3m0" | "e4m3" | "bf16" | "fp32"
     seed: int = 0
 
@@ -127,8 +127,17 @@ def fill_span(g: torch.Tensor, mom: torch.Tensor, w_send: List[torch.Tensor],
         gc = _randn(k, device, _seed(base_seed, unit, -1, "g", c)) * 0.02
         g[lo:hi] = gc
         mom[lo:hi] = 0
+        rho, common = 0.0, None
+        if delta.startswith("shared"):
+            # replicas' outer gradients correlate with coefficient rho (one common component)
+            rho = float(delta[len("shared"):]) / 100.0
+            common = _randn(k, device, _seed(base_seed, unit, -2, "shared", c)) * 1e-3
         for m in range(len(w_send)):
-            d = _delta(delta, k, device, _seed(base_seed, unit, m, "delta", c))
+            if common is not None:
+                own = _delta("normal", k, device, _seed(base_seed, unit, m, "delta", c))
+                d = common * rho ** 0.5 + own * (1.0 - rho) ** 0.5
+            else:
+                d = _delta(delta, k, device, _seed(base_seed, unit, m, "delta", c))
             ws = (gc - d).to(torch.bfloat16)
             w_send[m][lo:hi] = ws
             if tau > 0:
