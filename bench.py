@@ -44,7 +44,7 @@ class State:
     """Flat model arrays in HBM and the plan of one workload."""
 
     def __init__(self, wl, sdl, workloads, torch, fragment: int, M: int):
-        self.wl, self.M = wl, M
+        self.wl, self.M, self.fragment = wl, M, fragment
         dev = "cuda"
         if wl.shape is None:
             numel, block, L = [wl.flat_numel], [0], 1
@@ -220,6 +220,15 @@ def extras(st, fmt, wl, M, torch, sdl, args):
     dst = torch.empty_like(src)
     t = time_gpu(torch, lambda: sdl.sdl_copy_bytes(dst, src, nbytes), steps, warm)
     res["copy_kernel"] = {"ms": t, "GB/s": 2 * nbytes / t / 1e6, "bytes": nbytes}
+    # diagnostics: cosine similarity of the replicas' outer gradients, per span and for the whole fragment
+    # (reads 4 + 2M bytes per parameter)
+    frag = st.fragment
+    n_spans = len(st.spans)
+    span_res, work = sdl.alloc_cosine(M, n_spans)
+    frag_res = torch.empty(sdl.cosine_result_doubles(M), dtype=torch.float64, device="cuda")
+    t = time_gpu(torch, lambda: sdl.sdl_outer_grad_cosine_plan(st.plan, frag, st.g, st.w_send, span_res, frag_res, work),
+                 steps, warm)
+    res["outer_grad_cosine_fragment"] = {"ms": t, "GB/s": (4 + 2 * M) * st.n / t / 1e6, "spans": n_spans}
     return res
 
 

@@ -321,6 +321,47 @@ int sdl_offload_flush(sdl_offload_t* pool, void* compute_stream, void* copy_stre
 int sdl_engine_bind_offload(sdl_engine_t* engine, sdl_offload_t* pool, void* const* w_base, void* const* codes,
                             void* const* scales, void* copy_stream, uint32_t lookahead);
 
+/* ---- Diagnostics: cosine similarity between the replicas' outer gradients ----------
+ *
+ * Appendix, paragraph on the outer gradients' cosine similarity (figures per model scale, for
+ * the embedding, for everything else, and per transformer layer).  For one set of parameters
+ * and M replicas:
+ *     Delta_m   = g - float(w[m])                  fp32, Algorithm 2's outer gradient
+ *     G[a][b]   = sum_i Delta_a[i] * Delta_b[i]    fp64 products and sums
+ *     cos[a][b] = G[a][b] / (sqrt(G[a][a]) * sqrt(G[b][b])),  0 when either norm is 0
+ *     mean      = average of cos[a][b] over the pairs a < b (0 when M == 1)
+ * A result is SDL_COSINE_RESULT_DOUBLES(M) = 2*M*M + 1 doubles in device memory: G (row
+ * major), then cos (row major), then mean.  Summation order is fixed by the sizes alone, so a
+ * call is reproducible bit for bit; it differs from a sequential sum by fp64 rounding only.
+ * Reads 4 + 2*M bytes per parameter and writes nothing but the result.
+ *
+ * workspace: device memory of at least sdl_cosine_workspace_bytes(M, n_sets) bytes, 8-byte
+ * aligned, owned by the caller, contents irrelevant before and after the call.
+ * Errors: SDL_ERR_INVALID_ARG (null pointer, M == 0 or > SDL_MAX_WORKERS, workspace too
+ * small, p out of range), SDL_ERR_ALIGNMENT (result or workspace not 8-byte aligned),
+ * SDL_ERR_DEVICE (launch failure).  numel == 0 gives G = 0, cos = 0, mean = 0. */
+#define SDL_COSINE_RESULT_DOUBLES(M) (2u * (M) * (M) + 1u)
+size_t sdl_cosine_workspace_bytes(uint32_t M, uint32_t n_sets);
+
+/* One set: the numel parameters at g, w[m] (device pointers; w[m] bf16). */
+int sdl_outer_grad_cosine(const float* g, const void* const* w, uint32_t M, uint64_t numel, double* result,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* Fragment p of a plan, on the flat model at g_base / w_base[m]: one result per span of the
+ * fragment (= per transformer layer, embedding or head; order and units as
+ * sdl_plan_fragment_spans reports them) in span_results[n_spans][2*M*M+1], and the result of
+ * the whole fragment in fragment_result[2*M*M+1].  span_results may be null. */
+int sdl_outer_grad_cosine_plan(const sdl_plan_t* plan, uint32_t p, const float* g_base, const void* const* w_base,
+                               uint32_t M, double* span_results, double* fragment_result, void* workspace,
+                               size_t workspace_bytes, void* stream);
+
+/* Result of the union of n_sets disjoint parameter sets from their results (device memory,
+ * results[k] at results + k * stride_doubles): the Gram matrices add, cos and mean follow.
+ * This is how "all fragments but the embedding" is formed from per-fragment or per-span
+ * results.  Needs no workspace. */
+int sdl_cosine_combine(const double* results, uint64_t stride_doubles, uint32_t n_sets, uint32_t M, double* result,
+                       void* stream);
+
 /* Plain device-to-device streaming copy of nbytes (a multiple of 16; both pointers
  * 16-byte aligned).  Not part of the method: it is the yardstick against which the
  * achieved memory bandwidth of the calls above is judged (2 * nbytes of traffic). */

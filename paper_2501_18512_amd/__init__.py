@@ -104,6 +104,11 @@ def _load() -> ctypes.CDLL:
     lib.sdl_offload_flush.argtypes = [vp, vp, vp]
     lib.sdl_engine_bind_offload.argtypes = [vp, vp, pp, pp, pp, vp, u32]
     lib.sdl_copy_bytes.argtypes = [vp, vp, u64, vp]
+    lib.sdl_cosine_workspace_bytes.argtypes = [u32, u32]
+    lib.sdl_cosine_workspace_bytes.restype = ctypes.c_size_t
+    lib.sdl_outer_grad_cosine.argtypes = [vp, pp, u32, u64, vp, vp, ctypes.c_size_t, vp]
+    lib.sdl_outer_grad_cosine_plan.argtypes = [vp, u32, vp, pp, u32, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.sdl_cosine_combine.argtypes = [vp, u64, u32, u32, vp, vp]
     lib.sdl_status_string.argtypes = [ctypes.c_int]
     lib.sdl_status_string.restype = ctypes.c_char_p
     return lib
@@ -468,6 +473,49 @@ def sdl_engine_bind_offload(engine: Engine, pool: Offload, w_base, codes=None, s
 def sdl_copy_bytes(dst, src, nbytes: int, stream=None):
     _require_device(dst, src)
     _check(_lib.sdl_copy_bytes(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "sdl_copy_bytes")
+
+
+def sdl_cosine_workspace_bytes(M: int, n_sets: int) -> int:
+    return _lib.sdl_cosine_workspace_bytes(M, n_sets)
+
+
+def cosine_result_doubles(M: int) -> int:
+    """SDL_COSINE_RESULT_DOUBLES: Gram matrix, cosine matrix, mean over pairs."""
+    return 2 * M * M + 1
+
+
+def alloc_cosine(M: int, n_sets: int = 1, device="cuda"):
+    """Device buffers for the cosine calls: (results [n_sets, 2*M*M+1] fp64, workspace uint8)."""
+    results = torch.empty((n_sets, cosine_result_doubles(M)), dtype=torch.float64, device=device)
+    workspace = torch.empty(max(sdl_cosine_workspace_bytes(M, n_sets), 8), dtype=torch.uint8, device=device)
+    return results, workspace
+
+
+def split_cosine_result(result, M: int):
+    """(G [M, M], cos [M, M], mean) views of one result row."""
+    mm = M * M
+    return result[:mm].view(M, M), result[mm:2 * mm].view(M, M), result[2 * mm]
+
+
+def sdl_outer_grad_cosine(g, w, n: int, result, workspace, stream=None):
+    _require_device(g, *w, result, workspace)
+    _check(_lib.sdl_outer_grad_cosine(_ptr(g), _ptr_array(w), len(w), n, _ptr(result), _ptr(workspace),
+                                      workspace.numel(), _stream(stream)), "sdl_outer_grad_cosine")
+
+
+def sdl_outer_grad_cosine_plan(plan: "Plan", p: int, g_base, w_base, span_results, fragment_result, workspace,
+                               stream=None):
+    _require_device(g_base, *w_base, span_results, fragment_result, workspace)
+    _check(_lib.sdl_outer_grad_cosine_plan(plan._h, p, _ptr(g_base), _ptr_array(w_base), len(w_base),
+                                           _ptr(span_results), _ptr(fragment_result), _ptr(workspace),
+                                           workspace.numel(), _stream(stream)), "sdl_outer_grad_cosine_plan")
+
+
+def sdl_cosine_combine(results, n_sets: int, M: int, result, stream=None, stride_doubles: Optional[int] = None):
+    _require_device(results, result)
+    stride = cosine_result_doubles(M) if stride_doubles is None else stride_doubles
+    _check(_lib.sdl_cosine_combine(_ptr(results), stride, n_sets, M, _ptr(result), _stream(stream)),
+           "sdl_cosine_combine")
 
 
 def alloc_exchange(fmt: int, n: int, M: int, device="cuda"):
