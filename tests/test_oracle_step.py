@@ -246,3 +246,33 @@ def test_chunked_threads_same_result():
     assert np.array_equal(g, g2) and np.array_equal(mom, mom2)
     for a, b in zip(w_now, wn2):
         assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("kind,log2n,span_zero_min,span_bulk_min", [("student_t3", 22, 0.5, 0.45),
+                                                                     ("outliers", 18, 0.3, 0.27)])
+def test_scale_granularity_under_heavy_tails(kind, log2n, span_zero_min, span_bulk_min):
+    """Why the default scale covers 32 elements (Section 2.4 fixes only the 4-bit element): with one
+    scale per tensor, the few large entries of a heavy-tailed outer gradient set the scale and a
+    large share of the ordinary entries falls below half the smallest magnitude and is sent as
+    zero; with block scales the error of the ordinary entries stays at the format's own level
+    (mean relative error of nearest-power-of-two rounding, about 0.2)."""
+    import workloads
+    from oracle import FMT_E3M0_B128, FMT_E3M0_SPAN, cosine
+    n, M = 1 << log2n, 4                               # the largest entry of t(3) noise grows with the tensor
+    g, _, w, _ = workloads.make_span(n, M, tau=0, delta=kind, unit=5)
+    hg, hw = g.numpy(), [workloads.bf16_bits(x) for x in w]
+    d = cosine.outer_grads(hg, hw)
+    mean = d.astype(np.float64).mean(0)
+    bulk = np.abs(d).max(0) < 4e-3                      # entries where no replica has an outlier
+    assert bulk.mean() > 0.85
+    out = {}
+    for fmt in (FMT_E3M0, FMT_E3M0_B128, FMT_E3M0_SPAN):
+        codes, scales = oracle.quantize_outer_grad(hg, hw, fmt)
+        zero = float(np.mean((oracle.unpack_e3m0(codes[0], n) & 7) == 0))
+        got, unused = np.zeros(n, np.float32), np.zeros(n, np.float32)
+        oracle.dequant_reduce_nesterov(unused, got, codes, scales, fmt, 1.0, 0.0)    # mom' = mean of the decoded
+        err = np.linalg.norm((got - mean)[bulk]) / np.linalg.norm(mean[bulk])
+        out[fmt] = (zero, err)
+    assert out[FMT_E3M0][0] < 0.05 and out[FMT_E3M0][1] < 0.26
+    assert out[FMT_E3M0_B128][0] < 0.08 and out[FMT_E3M0_B128][1] < 0.26
+    assert out[FMT_E3M0_SPAN][0] > span_zero_min and out[FMT_E3M0_SPAN][1] > span_bulk_min
