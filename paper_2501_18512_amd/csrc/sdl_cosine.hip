@@ -35,6 +35,8 @@ constexpr int kWave = 64;
 constexpr int kTile = kLaneElems * kWave;       // 512
 constexpr int kBlockM = 8;                      // replicas per side of one launch's block of the matrix
 constexpr int kMaxSets = 48;                    // parameter sets per launch
+constexpr int kWindows = 48;                    // windows a launch's sets are cut into (at least one per set)
+constexpr int kMaxPieces = kMaxSets + kWindows;
 constexpr uint32_t kGroups = 8192;              // workgroups per launch, shared out among the sets (32 per compute unit)
 constexpr uint32_t kMaxGroups = 8192;           // what the workspace is sized for
 
@@ -51,6 +53,17 @@ struct Set {
     uint32_t G;          // workgroups of this set (>= 1)
 };
 
+// What the kernel walks: a set, or a window of a large set (tile aligned), with its own
+// share of the set's workgroups.
+struct Piece {
+    uint64_t offset;
+    uint64_t numel;
+    uint32_t first_wg;
+    uint32_t G;
+    uint32_t fast;       // every array is 16-byte aligned at the piece's start
+    uint32_t pad_;
+};
+
 struct GramArgs {
     const float* g;
     const uint16_t* wr[kBlockM];   // replicas of the block's rows
@@ -58,9 +71,8 @@ struct GramArgs {
     double* partial;               // [workgroup of the launch][M*M]
     uint32_t M;                    // side of the whole matrix
     uint32_t r0, c0;               // first row / column of this block
-    uint32_t n_sets;
-    uint64_t fast;                 // bit s: every array of set s is 16-byte aligned at its start
-    Set sets[kMaxSets];
+    uint32_t n_pieces;
+    Piece pieces[kMaxPieces];
 };
 
 __device__ __forceinline__ float u2f(uint32_t u) { return __builtin_bit_cast(float, u); }
@@ -139,10 +151,10 @@ __global__ void __launch_bounds__(kWave) sdl_gram_kernel(const GramArgs a)
     constexpr int NW = DIAG ? MR : MR + MC;
     const uint32_t lane = threadIdx.x;
     uint32_t s = 0;
-    while (s + 1 < a.n_sets && blockIdx.x >= a.sets[s + 1].first_wg) ++s;
-    const Set set = a.sets[s];
+    while (s + 1 < a.n_pieces && blockIdx.x >= a.pieces[s + 1].first_wg) ++s;
+    const Piece set = a.pieces[s];
     const uint32_t k = blockIdx.x - set.first_wg;
-    const bool fast = (a.fast >> s) & 1u;
+    const bool fast = set.fast != 0u;
     const uint64_t n_tiles = (set.numel + kTile - 1) / kTile;
 
     const uint16_t* w[NW];
@@ -182,12 +194,14 @@ __global__ void __launch_bounds__(kWave) sdl_gram_kernel(const GramArgs a)
     };
 
 #if SDL_GRAM_PREFETCH
+    // workgroup k's tiles: first, first + step, ... below end
+    const uint64_t first = k, step = set.G, end = n_tiles;
     TileRegs<NW> cur;
-    if (k < n_tiles) load_tile<NW>(cur, a.g, w, set.offset + (uint64_t)k * kTile, valid_of(k), fast, lane);
-    for (uint64_t t = k; t < n_tiles; t += set.G) {
+    if (first < end) load_tile<NW>(cur, a.g, w, set.offset + first * kTile, valid_of(first), fast, lane);
+    for (uint64_t t = first; t < end; t += step) {
         TileRegs<NW> nxt = cur;
-        const uint64_t tn = t + set.G;
-        if (tn < n_tiles) load_tile<NW>(nxt, a.g, w, set.offset + tn * kTile, valid_of(tn), fast, lane);
+        const uint64_t tn = t + step;
+        if (tn < end) load_tile<NW>(nxt, a.g, w, set.offset + tn * kTile, valid_of(tn), fast, lane);
         consume(cur);
         cur = nxt;
     }
@@ -210,17 +224,22 @@ __global__ void __launch_bounds__(kWave) sdl_gram_kernel(const GramArgs a)
 }
 
 // What each output of the finalize kernel adds up.
+constexpr uint32_t kFinChunk = 64;                                        // matrices one first-level output adds
+constexpr int kMaxFin = kMaxGroups / kFinChunk + 2 * kMaxSets + 2;        // outputs per finalize launch
+
 struct FinArgs {
     const double* in;              // matrices of M*M doubles (only a <= b is read), stride_k doubles apart
-    double* out;                   // output o: G, cos, mean at out + o * (2*M*M + 1)
+    double* out;                   // output o at out + o * out_stride
     uint64_t stride_k;
+    uint64_t out_stride;
     uint32_t M;
-    uint32_t pad_;
-    uint32_t first[kMaxSets];      // output o adds the matrices first[o] .. first[o] + count[o] - 1
-    uint32_t count[kMaxSets];
+    uint32_t emit;                 // 1: G, cos, mean (2*M*M + 1 doubles); 0: G only (M*M doubles)
+    uint32_t first[kMaxFin];       // output o adds the matrices first[o] .. first[o] + count[o] - 1
+    uint32_t count[kMaxFin];
 };
 
-// One workgroup per output.
+// One workgroup per output.  A lane adds every 64th matrix of its output's range, so a range
+// should be short: long ranges go through a first level of kFinChunk matrices per output.
 __global__ void __launch_bounds__(256) sdl_gram_finalize(const FinArgs f)
 {
     __shared__ double G[SDL_MAX_WORKERS * SDL_MAX_WORKERS];
@@ -238,7 +257,11 @@ __global__ void __launch_bounds__(256) sdl_gram_finalize(const FinArgs f)
             if (lane == 0) { G[a * M + b] = s; G[b * M + a] = s; }
         }
     __syncthreads();
-    double* o = f.out + (uint64_t)blockIdx.x * SDL_COSINE_RESULT_DOUBLES(M);
+    double* o = f.out + (uint64_t)blockIdx.x * f.out_stride;
+    if (!f.emit) {
+        for (uint32_t i = threadIdx.x; i < M * M; i += 256) o[i] = G[i];
+        return;
+    }
     for (uint32_t i = threadIdx.x; i < M * M; i += 256) {
         const uint32_t a = i / M, b = i % M;
         const double den = __builtin_sqrt(G[a * M + a]) * __builtin_sqrt(G[b * M + b]);
@@ -259,6 +282,16 @@ __global__ void __launch_bounds__(256) sdl_gram_finalize(const FinArgs f)
 
 // ------------------------------------------------------------------ host side
 
+uint32_t windows_per_launch()
+{
+    // tuning knob for sweeps; the default is what ships
+    if (const char* e = std::getenv("SDL_TUNE_GRAM_WINDOWS")) {
+        const long v = std::strtol(e, nullptr, 10);
+        if (v >= 1 && v <= (long)kWindows) return (uint32_t)v;
+    }
+    return kWindows;
+}
+
 uint32_t groups_per_launch()
 {
     // tuning knob for sweeps; the default is what ships
@@ -272,7 +305,7 @@ uint32_t groups_per_launch()
 template <int MR, bool DIAG>
 int launch_block_c(int mc, const GramArgs& a, hipStream_t st)
 {
-    const dim3 grid(a.sets[a.n_sets - 1].first_wg + a.sets[a.n_sets - 1].G), block(kWave);
+    const dim3 grid(a.pieces[a.n_pieces - 1].first_wg + a.pieces[a.n_pieces - 1].G), block(kWave);
     if constexpr (DIAG) {
         hipLaunchKernelGGL((sdl_gram_kernel<MR, MR, true>), grid, block, 0, st, a);
     } else {
@@ -336,13 +369,31 @@ int launch_gram(const float* g, const void* const* w, uint32_t M, const Set* set
     a.g = g;
     a.partial = partial;
     a.M = M;
-    a.n_sets = n_sets;
+    // cut the sets into windows: about `windows` pieces per launch, shared out like the workgroups
+    const uint32_t windows = windows_per_launch();
+    uint64_t total_G = 0;
+    for (uint32_t s = 0; s < n_sets; ++s) total_G += sets[s].G;
     for (uint32_t s = 0; s < n_sets; ++s) {
-        a.sets[s] = sets[s];
-        bool fast = aligned16(g + sets[s].offset);
-        for (uint32_t m = 0; m < M; ++m)
-            fast = fast && aligned16(static_cast<const uint16_t*>(w[m]) + sets[s].offset);
-        if (fast) a.fast |= 1ull << s;
+        const uint64_t tiles = (sets[s].numel + kTile - 1) / kTile;
+        uint64_t nsub = total_G ? ((uint64_t)windows * sets[s].G + total_G / 2) / total_G : 1;
+        if (nsub > sets[s].G) nsub = sets[s].G;
+        if (nsub > tiles) nsub = tiles;
+        if (nsub < 1) nsub = 1;
+        const uint64_t tiles_per = (tiles + nsub - 1) / nsub;
+        for (uint64_t j = 0; j < nsub; ++j) {
+            Piece& pc = a.pieces[a.n_pieces++];
+            const uint64_t e0 = j * tiles_per * kTile;
+            const uint64_t e1 = (j + 1) * tiles_per * kTile < sets[s].numel ? (j + 1) * tiles_per * kTile : sets[s].numel;
+            pc.offset = sets[s].offset + (e0 < sets[s].numel ? e0 : sets[s].numel);
+            pc.numel = e1 > e0 ? e1 - e0 : 0;
+            const uint32_t w0 = (uint32_t)((uint64_t)sets[s].G * j / nsub), w1 = (uint32_t)((uint64_t)sets[s].G * (j + 1) / nsub);
+            pc.first_wg = sets[s].first_wg + w0;
+            pc.G = w1 - w0;
+            bool fast = aligned16(g + pc.offset);
+            for (uint32_t m = 0; m < M; ++m)
+                fast = fast && aligned16(static_cast<const uint16_t*>(w[m]) + pc.offset);
+            pc.fast = fast ? 1u : 0u;
+        }
     }
     // the matrix in blocks of up to 8 x 8 replicas: diagonal blocks, then the blocks above them
     for (uint32_t r0 = 0; r0 < M; r0 += kBlockM) {
@@ -362,17 +413,53 @@ int launch_gram(const float* g, const void* const* w, uint32_t M, const Set* set
     return SDL_OK;
 }
 
-// One result per set from the partial matrices of its workgroups.
-int finalize_sets(const double* partial, const Set* sets, uint32_t n_sets, uint32_t M, double* out, hipStream_t st)
+int launch_finalize(const FinArgs& f, uint32_t n_out, hipStream_t st)
 {
-    FinArgs f{};
-    f.in = partial;
-    f.out = out;
-    f.stride_k = (uint64_t)M * M;
-    f.M = M;
-    for (uint32_t s = 0; s < n_sets; ++s) { f.first[s] = sets[s].first_wg; f.count[s] = sets[s].G; }
-    hipLaunchKernelGGL(sdl_gram_finalize, dim3(n_sets), dim3(256), 0, st, f);
+    hipLaunchKernelGGL(sdl_gram_finalize, dim3(n_out), dim3(256), 0, st, f);
     return hipGetLastError() == hipSuccess ? SDL_OK : SDL_ERR_DEVICE;
+}
+
+// One result per set from the partial matrices of its workgroups.  Sets with many workgroups
+// are first added up in chunks of kFinChunk matrices (into tmp), so that no lane of the
+// finalize kernel walks a long range.
+int finalize_sets(const double* partial, const Set* sets, uint32_t n_sets, uint32_t M, double* out, double* tmp,
+                  hipStream_t st)
+{
+    const uint64_t mm = (uint64_t)M * M;
+    bool two_level = false;
+    for (uint32_t s = 0; s < n_sets; ++s) two_level = two_level || sets[s].G > 2 * kFinChunk;
+    FinArgs last{};
+    last.out = out;
+    last.stride_k = mm;
+    last.out_stride = SDL_COSINE_RESULT_DOUBLES(M);
+    last.M = M;
+    last.emit = 1;
+    if (!two_level) {
+        last.in = partial;
+        for (uint32_t s = 0; s < n_sets; ++s) { last.first[s] = sets[s].first_wg; last.count[s] = sets[s].G; }
+        return launch_finalize(last, n_sets, st);
+    }
+    FinArgs lvl1{};
+    lvl1.in = partial;
+    lvl1.out = tmp;
+    lvl1.stride_k = mm;
+    lvl1.out_stride = mm;
+    lvl1.M = M;
+    lvl1.emit = 0;
+    uint32_t n = 0;
+    for (uint32_t s = 0; s < n_sets; ++s) {
+        last.first[s] = n;
+        for (uint32_t c = 0; c < sets[s].G; c += kFinChunk) {
+            lvl1.first[n] = sets[s].first_wg + c;
+            lvl1.count[n] = sets[s].G - c < kFinChunk ? sets[s].G - c : kFinChunk;
+            ++n;
+        }
+        last.count[s] = n - last.first[s];
+    }
+    int rc = launch_finalize(lvl1, n, st);
+    if (rc != SDL_OK) return rc;
+    last.in = tmp;
+    return launch_finalize(last, n_sets, st);
 }
 
 // One result from the Gram matrices of `count` results that lie stride doubles apart.
@@ -382,11 +469,26 @@ int finalize_union(const double* results, uint64_t stride, uint32_t count, uint3
     f.in = results;
     f.out = out;
     f.stride_k = stride;
+    f.out_stride = SDL_COSINE_RESULT_DOUBLES(M);
     f.M = M;
+    f.emit = 1;
     f.first[0] = 0;
     f.count[0] = count;
-    hipLaunchKernelGGL(sdl_gram_finalize, dim3(1), dim3(256), 0, st, f);
-    return hipGetLastError() == hipSuccess ? SDL_OK : SDL_ERR_DEVICE;
+    return launch_finalize(f, 1, st);
+}
+
+// Workspace layout, in M x M matrices: the partial matrices of every launch, then the
+// first-level sums of the finalize step; then (plan-level call without span_results) one
+// result per set.
+size_t partial_mats(size_t n_sets)
+{
+    const size_t launches = (n_sets + kMaxSets - 1) / kMaxSets;
+    return launches * kMaxGroups + n_sets;
+}
+size_t tmp_mats(size_t n_sets)
+{
+    const size_t launches = (n_sets + kMaxSets - 1) / kMaxSets;
+    return launches * (kMaxGroups / kFinChunk + 2) + 2 * n_sets;
 }
 
 int check_common(const void* g, const void* const* w, uint32_t M, const void* workspace)
@@ -405,11 +507,8 @@ extern "C" {
 size_t sdl_cosine_workspace_bytes(uint32_t M, uint32_t n_sets)
 {
     if (M == 0 || M > SDL_MAX_WORKERS) return 0;
-    // one partial matrix per workgroup of every launch, plus one result per set for the
-    // plan-level call when the caller does not ask for them
-    const size_t launches = ((size_t)n_sets + kMaxSets - 1) / kMaxSets;
-    const size_t groups = launches * kMaxGroups + n_sets;
-    return (groups * M * M + (size_t)n_sets * SDL_COSINE_RESULT_DOUBLES(M)) * sizeof(double);
+    return ((partial_mats(n_sets) + tmp_mats(n_sets)) * M * M + (size_t)n_sets * SDL_COSINE_RESULT_DOUBLES(M))
+           * sizeof(double);
 }
 
 int sdl_outer_grad_cosine(const float* g, const void* const* w, uint32_t M, uint64_t numel, double* result,
@@ -424,9 +523,10 @@ int sdl_outer_grad_cosine(const float* g, const void* const* w, uint32_t M, uint
     Set set{0, numel, 0, 0};
     share_groups(&set, 1, groups_per_launch());
     double* partial = static_cast<double*>(workspace);
+    double* tmp = partial + partial_mats(1) * M * M;
     rc = launch_gram(g, w, M, &set, 1, partial, st);
     if (rc != SDL_OK) return rc;
-    return finalize_sets(partial, &set, 1, M, result, st);
+    return finalize_sets(partial, &set, 1, M, result, tmp, st);
 }
 
 int sdl_outer_grad_cosine_plan(const sdl_plan_t* plan, uint32_t p, const float* g_base, const void* const* w_base,
@@ -447,9 +547,9 @@ int sdl_outer_grad_cosine_plan(const sdl_plan_t* plan, uint32_t p, const float* 
     const uint32_t groups = groups_per_launch();
     const uint64_t mm = (uint64_t)M * M, R = SDL_COSINE_RESULT_DOUBLES(M);
     double* partial = static_cast<double*>(workspace);
-    const size_t launches = ((size_t)n_spans + kMaxSets - 1) / kMaxSets;
-    double* per_span = span_results ? span_results : partial + (launches * kMaxGroups + n_spans) * mm;
-    uint64_t used = 0;   // partial matrices handed out so far
+    double* tmp = partial + partial_mats(n_spans) * mm;
+    double* per_span = span_results ? span_results : tmp + tmp_mats(n_spans) * mm;
+    uint64_t used = 0, used_tmp = 0;   // matrices handed out so far
     for (uint32_t s0 = 0; s0 < n_spans; s0 += kMaxSets) {
         const uint32_t ns = n_spans - s0 < (uint32_t)kMaxSets ? n_spans - s0 : (uint32_t)kMaxSets;
         Set sets[kMaxSets];
@@ -458,9 +558,10 @@ int sdl_outer_grad_cosine_plan(const sdl_plan_t* plan, uint32_t p, const float* 
         double* part = partial + used * mm;
         rc = launch_gram(g_base, w_base, M, sets, ns, part, st);
         if (rc != SDL_OK) return rc;
-        rc = finalize_sets(part, sets, ns, M, per_span + (uint64_t)s0 * R, st);
+        rc = finalize_sets(part, sets, ns, M, per_span + (uint64_t)s0 * R, tmp + used_tmp * mm, st);
         if (rc != SDL_OK) return rc;
         used += n_wg;
+        used_tmp += n_wg / kFinChunk + ns;
     }
     // the fragment: Gram matrices of its spans added in span order
     return finalize_union(per_span, R, n_spans, M, fragment_result, st);
