@@ -98,6 +98,8 @@ def main() -> int:
                     help="also time the receive side and the fused step over M in {1,2,4,8} x {e3m0,e4m3,bf16}")
     ap.add_argument("--offload", action="store_true",
                     help="also time the fragment step with g / mom staged from pinned host memory")
+    ap.add_argument("--engine", action="store_true",
+                    help="also walk the schedule driver over whole outer rounds (all P fragments, messages in HBM)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the M workers are M replicas resident in one "
@@ -169,6 +171,8 @@ def main() -> int:
         out["sweep"] = sweep(st, frag, wl, M, torch, sdl, args)
     if args.offload:
         out["offload"] = offload_timing(st, frag, fmt, wl, M, torch, sdl, args)
+    if args.engine:
+        out["engine"] = engine_timing(st, fmt, wl, M, torch, sdl, workloads)
     print(json.dumps(out))
     return 0
 
@@ -299,6 +303,54 @@ def offload_timing(st, frag, fmt, wl, M, torch, sdl, args):
         res[name] = {"ms": ms, "GB/s": (8 * st.n if name != "staged_step" else
                                         algorithmic_bytes_per_param(M, wl.tau) * st.n) / ms / 1e6}
     return res
+
+
+def engine_timing(st, fmt, wl, M, torch, sdl, workloads):
+    """Algorithm 2's outer schedule for the whole model: the engine is stepped through three periods of
+    H inner steps (inner steps themselves are not part of this build: nothing runs between the calls),
+    every fragment sends once and receives once per period.  Reports the device time of one period's
+    outer work and the host time the driver spends per inner step."""
+    P = st.plan.num_fragments
+    for p in range(P):                     # fill the fragments the main measurement left empty
+        if p == st.fragment:
+            continue
+        for off, n, unit in sdl.sdl_plan_fragment_spans(st.plan, p):
+            sl = slice(off, off + n)
+            workloads.fill_span(st.g[sl], st.mom[sl], [w[sl] for w in st.w_send], [w[sl] for w in st.w_now],
+                                unit=unit, tau=wl.tau, delta=wl.delta, base_seed=wl.seed)
+    eng = sdl.sdl_engine_create(st.plan, wl.H, [wl.tau] * M, fmt, wl.lr, wl.mu, wl.alpha)
+    codes, scales = [], []
+    for p in range(P):
+        cb, sb = sdl.sdl_plan_message_bytes(st.plan, p, fmt)
+        for _ in range(M):
+            codes.append(torch.empty(max(cb, 16), dtype=torch.uint8, device="cuda"))
+            scales.append(torch.empty(max(sb, 16), dtype=torch.uint8, device="cuda"))
+    # the engine works on the live replicas: the same arrays serve as w at the send and at the receive step
+    sdl.sdl_engine_bind(eng, st.g, st.mom, st.w_now, codes, scales)
+    total = st.plan.total_numel
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    periods, host = [], []
+    t = 0
+    for period in range(3):
+        torch.cuda.synchronize()
+        ev0.record()
+        h0 = time.perf_counter()
+        events = 0
+        for _ in range(wl.H):
+            t += 1
+            sent, received = sdl.sdl_engine_step(eng, t)
+            events += sent + received
+        host.append((time.perf_counter() - h0) / wl.H)
+        ev1.record()
+        torch.cuda.synchronize()
+        periods.append((ev0.elapsed_time(ev1), events))
+    ms, events = periods[-1]               # a steady-state period: P sends and P receives
+    c = sum(sdl.sdl_plan_message_bytes(st.plan, p, fmt)[i] for p in range(P) for i in (0, 1)) / total
+    bytes_per_param = (4 + 2 * M + M * c) + (16 + M * c + 4 * M) if wl.tau > 0 else algorithmic_bytes_per_param(M, 0)
+    return {"fragments": P, "model_params": total, "H": wl.H, "tau": wl.tau, "events_per_period": events,
+            "outer_work_ms_per_period": ms, "params_per_s": total / (ms * 1e-3),
+            "GB/s": bytes_per_param * total / ms / 1e6, "bytes_per_param": bytes_per_param,
+            "host_us_per_inner_step": 1e6 * host[-1]}
 
 
 if __name__ == "__main__":
