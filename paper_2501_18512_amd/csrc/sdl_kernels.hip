@@ -262,11 +262,14 @@ __device__ __forceinline__ void decode_e3m0(uint32_t c0, float scale, float (&dq
         dq[j] = u2f(((nib & 8u) << 28) | f2u(val * scale));
     }
 }
+// EXACT = false: the conversion instruction alone, which reads the byte values 0x7f / 0xff as
+// NaN; the caller then repeats the decode with EXACT = true wherever a NaN shows up in the sum.
+template <bool EXACT>
 __device__ __forceinline__ void decode_e4m3(uint32_t c0, float scale, float (&dq)[kVec])
 {
     // codes 0x7f / 0xff never come out of the encoder; read as a number (480) like every other
     // code rather than as the NaN the conversion instruction makes of them
-    if (((c0 & 0x7f7f7f7fu) + 0x01010101u) & 0x80808080u) {
+    if (EXACT && (((c0 & 0x7f7f7f7fu) + 0x01010101u) & 0x80808080u)) {
 #pragma unroll
         for (int j = 0; j < kVec; ++j) {
             const uint32_t byte = (c0 >> (8 * j)) & 255u;
@@ -367,7 +370,10 @@ struct TileIO {
     __device__ __forceinline__ void load_wn(uint32_t m, int row, uint32_t (&u)[2]) const { ld_bf16(a.w_now[m] + t0, row, u); }
     __device__ __forceinline__ void store_wn(uint32_t m, int row, const uint32_t (&u)[2]) const { st_bf16(a.w_now[m] + t0, row, u); }
 
-    template <int FMT> __device__ __forceinline__ void load_message(uint32_t m, int row, float (&dq)[kVec]) const
+    // E4M3 only: with EXACT = false the two byte values the encoder never writes decode to NaN
+    static constexpr bool kHasInexactDecode = true;
+    template <int FMT, bool EXACT = true>
+    __device__ __forceinline__ void load_message(uint32_t m, int row, float (&dq)[kVec]) const
     {
         const uint8_t* codes = a.codes[m];
         if constexpr (FMT == SDL_FMT_FP32) {
@@ -386,7 +392,7 @@ struct TileIO {
             } else {
                 const uint32_t c0 = __builtin_amdgcn_raw_buffer_load_b32(rsrc(codes + tb, kGroup),
                                                                          (int)(row * kRow + lane * 4), 0, SDL_AUX_LD);
-                decode_e4m3(c0, scale, dq);
+                decode_e4m3<EXACT>(c0, scale, dq);
             }
         }
     }
@@ -485,7 +491,9 @@ struct GuardedIO {
     __device__ __forceinline__ void load_wn(uint32_t m, int row, uint32_t (&u)[2]) const { ld_bf16(a.w_now[m] + flat(row), valid(row), u); }
     __device__ __forceinline__ void store_wn(uint32_t m, int row, const uint32_t (&u)[2]) const { st_bf16(a.w_now[m] + flat(row), valid(row), u); }
 
-    template <int FMT> __device__ __forceinline__ void load_message(uint32_t m, int row, float (&dq)[kVec]) const
+    static constexpr bool kHasInexactDecode = false;
+    template <int FMT, bool EXACT = true>
+    __device__ __forceinline__ void load_message(uint32_t m, int row, float (&dq)[kVec]) const
     {
         const uint8_t* codes = a.codes[m];
         const uint64_t b = msg(row);
@@ -510,7 +518,7 @@ struct GuardedIO {
 #pragma unroll
                 for (int j = 0; j < kVec; ++j)
                     if (j < n) c0 |= (uint32_t)codes[b + j] << (8 * j);
-                decode_e4m3(c0, scale, dq);
+                decode_e4m3<true>(c0, scale, dq);
             }
         }
     }
@@ -625,7 +633,7 @@ __device__ __forceinline__ void process(const Args& a, const IO& io)
             for (int r = 0; r < kRows; ++r) {
                 float dq[kVec];
                 if constexpr (MODE == kReduce || MODE == kReceive) {
-                    io.template load_message<FMT>(m, r, dq);
+                    io.template load_message<FMT, !(FMT == SDL_FMT_E4M3 && IO::kHasInexactDecode)>(m, r, dq);
                 } else {
                     if constexpr (MT == 0) io.load_ws(m, r, ws[0][r]);
                     float w[kVec], d[kVec];
@@ -641,6 +649,27 @@ __device__ __forceinline__ void process(const Args& a, const IO& io)
                 }
 #pragma unroll
                 for (int j = 0; j < kVec; ++j) acc[r][j] = acc[r][j] + dq[j];
+            }
+        }
+    }
+
+    // E4M3 messages were decoded by the conversion instruction alone.  It turns the two byte
+    // values that the encoder never writes into NaN, which survives the sum: where any lane of
+    // the wavefront sees a NaN (rare: a foreign message, or a block that really holds NaN), the
+    // row is decoded again, exactly, from the messages in memory.
+    if constexpr ((MODE == kReduce || MODE == kReceive) && FMT == SDL_FMT_E4M3 && IO::kHasInexactDecode) {
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) {
+            const float t = (acc[r][0] + acc[r][1]) + (acc[r][2] + acc[r][3]);
+            if (__builtin_amdgcn_ballot_w64(t != t) != 0ull) {
+#pragma unroll
+                for (int j = 0; j < kVec; ++j) acc[r][j] = 0.0f;
+                for (uint32_t m = 0; m < M; ++m) {
+                    float dq[kVec];
+                    io.template load_message<FMT, true>(m, r, dq);
+#pragma unroll
+                    for (int j = 0; j < kVec; ++j) acc[r][j] = acc[r][j] + dq[j];
+                }
             }
         }
     }
