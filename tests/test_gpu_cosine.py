@@ -176,6 +176,33 @@ def test_full_size_1b_fragment():
     _compare(frag, M, G, cos, mean, "1b fragment 1 from its spans")
 
 
+def test_stream_argument_and_graph_replay():
+    """The calls run on the caller's stream, allocate nothing and use no memset, so they can be
+    captured; every replay must give the eager result."""
+    n, M = 700_001, 3
+    g, w = _span(n, M)
+    eager, work = sdl.alloc_cosine(M)
+    sdl.sdl_outer_grad_cosine(g, w, n, eager[0], work)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    got, work2 = sdl.alloc_cosine(M)
+    sdl.sdl_outer_grad_cosine(g, w, n, got[0], work2, stream=side)
+    side.synchronize()
+    assert torch.equal(got.view(torch.int64), eager.view(torch.int64))
+    graph = torch.cuda.CUDAGraph()
+    captured, work3 = sdl.alloc_cosine(M)
+    with torch.cuda.graph(graph):
+        sdl.sdl_outer_grad_cosine(g, w, n, captured[0], work3)
+    for replay in range(3):
+        captured.zero_()
+        work3.fill_(replay)                      # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(captured.view(torch.int64), eager.view(torch.int64)), f"replay {replay}"
+
+
 def test_argument_errors():
     g, w = _span(1024, 2)
     result, work = sdl.alloc_cosine(2)
