@@ -169,3 +169,32 @@ def test_engine_rejects_bad_arguments():
     assert sdl.sdl_plan_message_bytes(plan, 0, sdl.FMT_E3M0) == (2 * 512 // 2, 2 * 512 // 32)
     assert sdl.sdl_plan_message_bytes(plan, 0, sdl.FMT_E3M0_B128) == (2 * 512 // 2, 2 * 512 // 128)
     assert sdl.sdl_plan_message_bytes(plan, 0, sdl.FMT_E3M0_SPAN) == (2 * 512 // 2, 2 * 4)
+
+
+def test_cosine_calls_reject_bad_arguments_before_launch():
+    lib, good = sdl._lib, 0x1000
+    ptrs = lambda xs: (ctypes.c_void_p * len(xs))(*xs)
+    assert sdl.sdl_cosine_workspace_bytes(0, 1) == 0 and sdl.sdl_cosine_workspace_bytes(17, 1) == 0
+    sizes = [sdl.sdl_cosine_workspace_bytes(M, 1) for M in range(1, 17)]
+    assert all(a < b for a, b in zip(sizes, sizes[1:])) and sizes[-1] < 64 << 20
+    assert sdl.sdl_cosine_workspace_bytes(4, 100) > sdl.sdl_cosine_workspace_bytes(4, 1)
+    need = sdl.sdl_cosine_workspace_bytes(2, 1)
+    call = lib.sdl_outer_grad_cosine
+    assert call(0, ptrs([good, good]), 2, 64, good, good, need, 0) == -1              # g missing
+    assert call(good, ptrs([good, 0]), 2, 64, good, good, need, 0) == -1              # a replica missing
+    assert call(good, ptrs([good] * 17), 17, 64, good, good, need, 0) == -1           # too many replicas
+    assert call(good, ptrs([good, good]), 2, 64, 0, good, need, 0) == -1              # result missing
+    assert call(good, ptrs([good, good]), 2, 64, good, 0, need, 0) == -1              # workspace missing
+    assert call(good, ptrs([good, good]), 2, 64, good, good, need - 1, 0) == -1       # workspace too small
+    assert call(good, ptrs([good, good]), 2, 64, good + 4, good, need, 0) == -3       # result not 8-byte aligned
+    assert call(good, ptrs([good, good]), 2, 64, good, good + 4, need, 0) == -3       # workspace not 8-byte aligned
+    plan = sdl.sdl_fragment_plan([64] * 6, list(range(6)), 6, 3, sdl.PATTERN_STRIDED, 10, 1)
+    need = sdl.sdl_cosine_workspace_bytes(2, 2)
+    pcall = lib.sdl_outer_grad_cosine_plan
+    assert pcall(plan._h, 3, good, ptrs([good, good]), 2, good, good, good, need, 0) == -1    # no such fragment
+    assert pcall(plan._h, 0, good, ptrs([good, good]), 2, good, 0, good, need, 0) == -1       # fragment result missing
+    assert pcall(plan._h, 0, good, ptrs([good, good]), 2, good, good, good, need - 1, 0) == -1
+    assert pcall(None, 0, good, ptrs([good, good]), 2, good, good, good, need, 0) == -1
+    assert lib.sdl_cosine_combine(good, 8, 3, 2, good, 0) == -1                               # stride shorter than a result
+    assert lib.sdl_cosine_combine(0, 9, 3, 2, good, 0) == -1
+    assert lib.sdl_cosine_combine(good, 9, 3, 0, good, 0) == -1
