@@ -159,13 +159,17 @@ struct BlockScale {
 template <int FMT>
 __device__ __forceinline__ BlockScale block_scale_from_exponent(uint32_t e_a)
 {
+    // written with single comparisons and selects: this runs once per scale block and replica,
+    // and as control flow it cost more than the codec of the block's elements
     constexpr uint32_t emax = is_e3m0(FMT) ? 4u : 8u;
     BlockScale b;
-    b.sb = e_a > emax ? e_a - emax : 0u;
-    b.degenerate = (e_a == 0u) || (e_a == 255u);
-    b.inv = b.degenerate ? 0.0f : u2f((254u - b.sb) << 23);
-    b.scale = b.sb ? u2f(b.sb << 23) : u2f(0x00400000u);       // 2^-127 is an fp32 subnormal
-    if (e_a == 255u) { b.sb = 255u; b.scale = u2f(0x7fc00000u); }
+    const uint32_t sb = e_a > emax ? e_a - emax : 0u;
+    const bool nan_block = e_a == 255u;
+    b.degenerate = (e_a - 1u) >= 254u;                          // 0 (zero / subnormal maximum) or 255 (Inf / NaN)
+    b.inv = b.degenerate ? 0.0f : u2f((254u - sb) << 23);
+    const uint32_t scale_bits = (sb << 23) > 0x00400000u ? (sb << 23) : 0x00400000u;   // 2^-127 is an fp32 subnormal
+    b.scale = u2f(nan_block ? 0x7fc00000u : scale_bits);
+    b.sb = nan_block ? 255u : sb;
     return b;
 }
 
@@ -238,11 +242,15 @@ __device__ __forceinline__ void encode(const float (&d)[kVec], float (&dq)[kVec]
                 const float val = y > 0.125f ? pw : 0.0f;          // half of the smallest magnitude
                 dq[j] = u2f(sign | f2u(val * b.scale));
                 if (want_codes) {
-                    // the code comes straight from the rounded bit pattern, not from val, so that a
-                    // kernel that only writes messages does not carry the decode arithmetic
-                    const int e = (int)(rr >> 23) - 124;
-                    const int ec = e < 1 ? 1 : (e > 7 ? 7 : e);
-                    const uint32_t E = y > 0.125f ? (uint32_t)ec : 0u;
+                    // the code comes straight from a rounded bit pattern, not from val, so that a
+                    // kernel that only writes messages does not carry the decode arithmetic: clamp
+                    // to [1/4, 16] first (exact: everything below rounds up to 1/4 or is the zero
+                    // code, everything above saturates), round as above with 4 added to the
+                    // exponent field, and the three low bits of the field are the code
+                    // (fields 125..131 -> 129..135 -> 1..7)
+                    const uint32_t cb = f2u(__builtin_amdgcn_fmed3f(y, 0.25f, 16.0f));
+                    const uint32_t rc = cb + 0x023fffffu + ((cb >> 23) & 1u);
+                    const uint32_t E = y > 0.125f ? (rc >> 23) & 7u : 0u;
                     packed |= ((sign >> 28) | E) << (4 * j);
                 }
             }
