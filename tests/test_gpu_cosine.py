@@ -176,6 +176,33 @@ def test_full_size_1b_fragment():
     _compare(frag, M, G, cos, mean, "1b fragment 1 from its spans")
 
 
+def test_more_than_2_to_the_31_parameters():
+    """The 4B shape as one set of 4,273,695,744 parameters (element indices beyond 2^31, byte offsets
+    beyond 2^34): the single call must agree with the sum of the per-span results of the plan-level
+    call, and the oracle checks the spans at the far end of the arrays one by one."""
+    import dataclasses
+    wl = dataclasses.replace(workloads.WORKLOADS["4b_p1"], delta="shared10", tau=0)
+    model = FlatModel(wl)
+    M, total = wl.M, model.plan.total_numel
+    assert total > 2 ** 31
+    whole, work = sdl.alloc_cosine(M)
+    sdl.sdl_outer_grad_cosine(model.g, model.w_send, total, whole[0], work)
+    spans = sdl.sdl_plan_fragment_spans(model.plan, 0)
+    span_results, work2 = sdl.alloc_cosine(M, len(spans))
+    frag = torch.empty(sdl.cosine_result_doubles(M), dtype=torch.float64, device=DEV)
+    sdl.sdl_outer_grad_cosine_plan(model.plan, 0, model.g, model.w_send, span_results, frag, work2)
+    torch.cuda.synchronize()
+    G1, cos1, mean1 = (x.cpu().numpy() for x in sdl.split_cosine_result(whole[0], M))
+    _compare(frag, M, G1, cos1, float(mean1), "4B: one set against the sum of its spans")
+    assert abs(float(mean1) - 0.1) < 0.01
+    for i in (len(spans) - 1, len(spans) - 2, len(spans) - 3):
+        off, n, unit = spans[i]
+        print(f"4B span {i}: unit {unit}, offset {off}, {n} parameters", flush=True)
+        G, cos, mean = ref.outer_grad_cosine(host_f32(model.g[off:off + n]),
+                                             [host_bits(w[off:off + n]) for w in model.w_send])
+        _compare(span_results[i], M, G, cos, mean, f"4B span {i}")
+
+
 def test_stream_argument_and_graph_replay():
     """The calls run on the caller's stream, allocate nothing and use no memset, so they can be
     captured; every replay must give the eager result."""
