@@ -212,10 +212,21 @@ int sdl_fragment_outer_step(float* g, float* mom, const void* const* w_send, voi
 /* Fused outer step of a whole fragment of a plan: every run of fragment p, in one
  * kernel launch per group of up to 16 runs.  The pointers are the bases of the flat model arrays
  * (element 0 of the model); run r is processed at element offset runs[r].offset.
- * Messages are not written.  SDL_FMT_E3M0_SPAN is not supported here (SDL_ERR_UNSUPPORTED). */
+ * Messages are not written.  SDL_FMT_E3M0_SPAN is not supported here (SDL_ERR_UNSUPPORTED): it needs the
+ * scale words that the _ex form below takes. */
 int sdl_fragment_outer_step_plan(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
                                  const void* const* w_send_base, void* const* w_now_base, uint32_t M,
                                  sdl_format_t fmt, float lr, float mu, float alpha, void* stream);
+
+/* The same with the optional outputs of sdl_fragment_outer_step: if codes_or_null is given the
+ * fragment's messages are also written, laid out as sdl_quantize_outer_grad_plan writes them
+ * (sdl_plan_message_bytes per replica); SDL_FMT_E3M0_SPAN is supported when scales_or_null is
+ * given (M device pointers, one 4-byte word per span of the fragment each: workspace, and the
+ * scale part of the messages). */
+int sdl_fragment_outer_step_plan_ex(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
+                                    const void* const* w_send_base, void* const* w_now_base, uint32_t M,
+                                    sdl_format_t fmt, float lr, float mu, float alpha, void* const* codes_or_null,
+                                    void* const* scales_or_null, void* stream);
 
 /* Fragment-level forms of the send-side and receive-side calls: every run of fragment p
  * of a plan, on the flat model arrays (bases = element 0 of the model).  The messages of a
@@ -248,7 +259,7 @@ int sdl_receive_outer_step_plan(const sdl_plan_t* plan, uint32_t p, float* g_bas
  *   - tau steps later: sdl_dequant_reduce_nesterov_plan, then sdl_merge_overlap_plan into
  *     the replicas as they are then (Section 2.3) -- as the single pass
  *     sdl_receive_outer_step_plan when all workers share one delay;
- *   - with tau = 0 for every worker: sdl_fragment_outer_step_plan at the send step.
+ *   - with tau = 0 for every worker: sdl_fragment_outer_step_plan_ex at the send step.
  * tau_m[m] < H is worker m's delay (Section 3.3.2: workers may receive the same update at
  * different steps); the mean and the Nesterov update happen once, at the smallest delay,
  * and each worker merges when its own delay expires.
@@ -256,7 +267,8 @@ int sdl_receive_outer_step_plan(const sdl_plan_t* plan, uint32_t p, float* g_bas
  * be fed in order without gaps (a skipped receive is reported as SDL_ERR_INVALID_ARG).
  * sdl_engine_bind: g_base, mom_base, w_base[M] = flat device arrays (the live replicas);
  * codes / scales = host arrays of P*M device pointers, entry p*M + m sized by
- * sdl_plan_message_bytes(plan, p, ...); both may be NULL when every delay is 0.
+ * sdl_plan_message_bytes(plan, p, ...); both may be NULL when every delay is 0 (except that
+ * SDL_FMT_E3M0_SPAN always needs scales: its scale words are workspace of the fused call).
  * n_sent / n_received (optional) count the fragments whose send / mean+Nesterov ran. */
 typedef struct sdl_engine sdl_engine_t;
 int sdl_engine_create(const sdl_plan_t* plan, uint32_t H, uint32_t M, const uint32_t* tau_m, sdl_format_t fmt,
@@ -279,6 +291,10 @@ uint64_t sdl_plan_staged_numel(const sdl_plan_t* plan, uint32_t p);
 int sdl_fragment_outer_step_staged(const sdl_plan_t* plan, uint32_t p, float* g_frag, float* mom_frag,
                                    const void* const* w_send_base, void* const* w_now_base, uint32_t M,
                                    sdl_format_t fmt, float lr, float mu, float alpha, void* stream);
+int sdl_fragment_outer_step_staged_ex(const sdl_plan_t* plan, uint32_t p, float* g_frag, float* mom_frag,
+                                      const void* const* w_send_base, void* const* w_now_base, uint32_t M,
+                                      sdl_format_t fmt, float lr, float mu, float alpha, void* const* codes_or_null,
+                                      void* const* scales_or_null, void* stream);
 int sdl_quantize_outer_grad_staged(const sdl_plan_t* plan, uint32_t p, const float* g_frag,
                                    const void* const* w_send_base, uint32_t M, sdl_format_t fmt,
                                    void* const* codes, void* const* scales, void* stream);

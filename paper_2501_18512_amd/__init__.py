@@ -88,6 +88,8 @@ def _load() -> ctypes.CDLL:
     lib.sdl_plan_staged_numel.argtypes = [vp, u32]
     lib.sdl_plan_staged_numel.restype = u64
     lib.sdl_fragment_outer_step_staged.argtypes = lib.sdl_fragment_outer_step_plan.argtypes
+    lib.sdl_fragment_outer_step_plan_ex.argtypes = [vp, u32, vp, vp, pp, pp, u32, ctypes.c_int, f32, f32, f32, pp, pp, vp]
+    lib.sdl_fragment_outer_step_staged_ex.argtypes = lib.sdl_fragment_outer_step_plan_ex.argtypes
     lib.sdl_quantize_outer_grad_staged.argtypes = lib.sdl_quantize_outer_grad_plan.argtypes
     lib.sdl_dequant_reduce_nesterov_staged.argtypes = lib.sdl_dequant_reduce_nesterov_plan.argtypes
     lib.sdl_merge_overlap_staged.argtypes = lib.sdl_merge_overlap_plan.argtypes
@@ -316,6 +318,30 @@ def sdl_fragment_outer_step_plan(plan: Plan, p: int, g_base, mom_base, w_send_ba
                                              _ptr_array(w_send_base), _ptr_array(w_now_base),
                                              len(w_send_base), fmt, lr, mu, alpha, _stream(stream)),
            "sdl_fragment_outer_step_plan")
+
+
+def sdl_fragment_outer_step_plan_ex(plan: Plan, p: int, g_base, mom_base, w_send_base, w_now_base,
+                                    fmt: int, lr: float, mu: float, alpha: float, codes=None, scales=None,
+                                    stream=None):
+    _require_device(g_base, mom_base, *w_send_base, *w_now_base, *(codes or []), *(scales or []))
+    if len(w_send_base) != len(w_now_base):
+        raise SdlError(-1, "sdl_fragment_outer_step_plan_ex")
+    _check(_lib.sdl_fragment_outer_step_plan_ex(plan._h, p, _ptr(g_base), _ptr(mom_base),
+                                                _ptr_array(w_send_base), _ptr_array(w_now_base),
+                                                len(w_send_base), fmt, lr, mu, alpha, _ptr_array(codes),
+                                                _ptr_array(scales), _stream(stream)),
+           "sdl_fragment_outer_step_plan_ex")
+
+
+def sdl_fragment_outer_step_staged_ex(plan: Plan, p: int, g_frag, mom_frag, w_send_base, w_now_base,
+                                      fmt: int, lr: float, mu: float, alpha: float, codes=None, scales=None,
+                                      stream=None):
+    _require_device(g_frag, mom_frag, *w_send_base, *w_now_base, *(codes or []), *(scales or []))
+    _check(_lib.sdl_fragment_outer_step_staged_ex(plan._h, p, _ptr(g_frag), _ptr(mom_frag),
+                                                  _ptr_array(w_send_base), _ptr_array(w_now_base),
+                                                  len(w_send_base), fmt, lr, mu, alpha, _ptr_array(codes),
+                                                  _ptr_array(scales), _stream(stream)),
+           "sdl_fragment_outer_step_staged_ex")
 
 
 def sdl_plan_message_bytes(plan: Plan, p: int, fmt: int) -> Tuple[int, int]:

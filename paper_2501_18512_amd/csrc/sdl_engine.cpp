@@ -78,20 +78,20 @@ int sdl_engine_bind(sdl_engine_t* e, float* g_base, float* mom_base, void* const
 {
     if (!e || !g_base || !mom_base || !w_base) return SDL_ERR_INVALID_ARG;
     // without any delay the fused call is used, which keeps the messages in registers; the
-    // whole-span scale has no fused fragment call, so it always goes through messages
-    const bool need_messages = e->delay_max > 0 || e->fmt == SDL_FMT_E3M0_SPAN;
+    // whole-span scale still needs its scale words (as workspace)
+    const bool need_codes = e->delay_max > 0;
     const bool scaled = e->fmt >= SDL_FMT_E4M3;
-    if (need_messages && (!codes || (scaled && !scales))) return SDL_ERR_INVALID_ARG;
+    const bool need_scales = (need_codes && scaled) || e->fmt == SDL_FMT_E3M0_SPAN;
+    if ((need_codes && !codes) || (need_scales && !scales)) return SDL_ERR_INVALID_ARG;
     for (uint32_t m = 0; m < e->M; ++m)
         if (!w_base[m]) return SDL_ERR_INVALID_ARG;
-    if (need_messages)
-        for (size_t i = 0; i < (size_t)e->P * e->M; ++i)
-            if (!codes[i] || (scaled && !scales[i])) return SDL_ERR_INVALID_ARG;
+    for (size_t i = 0; i < (size_t)e->P * e->M; ++i)
+        if ((need_codes && !codes[i]) || (need_scales && !scales[i])) return SDL_ERR_INVALID_ARG;
     e->g = g_base; e->mom = mom_base;
     for (uint32_t m = 0; m < e->M; ++m) e->w[m] = w_base[m];
     for (size_t i = 0; i < (size_t)e->P * e->M; ++i) {
-        e->codes[i] = need_messages ? codes[i] : nullptr;
-        e->scales[i] = (need_messages && scaled) ? scales[i] : nullptr;
+        e->codes[i] = need_codes ? codes[i] : nullptr;
+        e->scales[i] = need_scales ? scales[i] : nullptr;
     }
     e->bound = true;
     return SDL_OK;
@@ -134,12 +134,14 @@ int sdl_engine_step(sdl_engine_t* e, uint64_t t, void* stream, uint32_t* n_sent,
         }
         if (sends) {
             if (e->sent_at[p] != 0) return SDL_ERR_INVALID_ARG;      // previous message not consumed: steps skipped
-            if (e->delay_max == 0 && e->fmt != SDL_FMT_E3M0_SPAN) {
-                // no overlap anywhere: the whole outer step at once
-                int rc = staged ? sdl_fragment_outer_step_staged(e->plan, p, g, mom, e->w.data(), e->w.data(), M,
-                                                                 e->fmt, e->lr, e->mu, e->alpha, stream)
-                                : sdl_fragment_outer_step_plan(e->plan, p, g, mom, e->w.data(), e->w.data(), M,
-                                                               e->fmt, e->lr, e->mu, e->alpha, stream);
+            if (e->delay_max == 0) {
+                // no overlap anywhere: the whole outer step at once, messages kept in registers (the
+                // whole-span scale uses the fragment's scale words as workspace)
+                void* const* work = e->fmt == SDL_FMT_E3M0_SPAN ? scales : nullptr;
+                int rc = staged ? sdl_fragment_outer_step_staged_ex(e->plan, p, g, mom, e->w.data(), e->w.data(), M,
+                                                                    e->fmt, e->lr, e->mu, e->alpha, nullptr, work, stream)
+                                : sdl_fragment_outer_step_plan_ex(e->plan, p, g, mom, e->w.data(), e->w.data(), M,
+                                                                  e->fmt, e->lr, e->mu, e->alpha, nullptr, work, stream);
                 if (rc != SDL_OK) return rc;
                 if (staged) {
                     rc = sdl_offload_release(e->offload, p, stream, e->copy_stream);

@@ -1023,6 +1023,34 @@ static int fill_fused_args(Args& a, float* g, float* mom, const void* const* w_s
     return SDL_OK;
 }
 
+// Optional message outputs of a fused call; the whole-span scale needs its scale words as
+// workspace even when no message is written.
+static int attach_fused_messages(Args& a, uint32_t M, sdl_format_t fmt, void* const* codes_or_null,
+                                 void* const* scales_or_null, bool* vec)
+{
+    if (codes_or_null) {
+        const bool scaled = is_scaled(fmt);
+        if (scaled && !scales_or_null) return SDL_ERR_INVALID_ARG;
+        for (uint32_t m = 0; m < M; ++m) {
+            if (!codes_or_null[m] || (scaled && !scales_or_null[m])) return SDL_ERR_INVALID_ARG;
+            if (!aligned(codes_or_null[m], code_align(fmt))) return SDL_ERR_ALIGNMENT;
+            *vec = *vec && aligned(codes_or_null[m], 16);
+            a.codes[m] = static_cast<uint8_t*>(codes_or_null[m]);
+            a.scales[m] = scaled ? static_cast<uint8_t*>(scales_or_null[m]) : nullptr;
+        }
+        a.emit = 1;
+    }
+    if (is_span_scaled(fmt)) {
+        if (!scales_or_null) return SDL_ERR_INVALID_ARG;
+        for (uint32_t m = 0; m < M; ++m) {
+            if (!scales_or_null[m]) return SDL_ERR_INVALID_ARG;
+            if (!aligned(scales_or_null[m], 4)) return SDL_ERR_ALIGNMENT;
+            a.scales[m] = static_cast<uint8_t*>(scales_or_null[m]);
+        }
+    }
+    return SDL_OK;
+}
+
 int sdl_fragment_outer_step(float* g, float* mom, const void* const* w_send, void* const* w_now,
                             uint32_t M, uint64_t n, sdl_format_t fmt, float lr, float mu, float alpha,
                             void* const* codes_or_null, void* const* scales_or_null, void* stream)
@@ -1032,27 +1060,8 @@ int sdl_fragment_outer_step(float* g, float* mom, const void* const* w_send, voi
     bool vec = false;
     int rc = fill_fused_args(a, g, mom, w_send, w_now, M, fmt, lr, mu, alpha, &vec);
     if (rc != SDL_OK) return rc;
-    if (codes_or_null) {
-        const bool scaled = is_scaled(fmt);
-        if (scaled && !scales_or_null) return SDL_ERR_INVALID_ARG;
-        for (uint32_t m = 0; m < M; ++m) {
-            if (!codes_or_null[m] || (scaled && !scales_or_null[m])) return SDL_ERR_INVALID_ARG;
-            if (!aligned(codes_or_null[m], code_align(fmt))) return SDL_ERR_ALIGNMENT;
-            vec = vec && aligned(codes_or_null[m], 16);
-            a.codes[m] = static_cast<uint8_t*>(codes_or_null[m]);
-            a.scales[m] = scaled ? static_cast<uint8_t*>(scales_or_null[m]) : nullptr;
-        }
-        a.emit = 1;
-    }
-    if (is_span_scaled(fmt)) {
-        // the whole-span scale needs its 4-byte word per replica even when no message is written
-        if (!scales_or_null) return SDL_ERR_INVALID_ARG;
-        for (uint32_t m = 0; m < M; ++m) {
-            if (!scales_or_null[m]) return SDL_ERR_INVALID_ARG;
-            if (!aligned(scales_or_null[m], 4)) return SDL_ERR_ALIGNMENT;
-            a.scales[m] = static_cast<uint8_t*>(scales_or_null[m]);
-        }
-    }
+    rc = attach_fused_messages(a, M, fmt, codes_or_null, scales_or_null, &vec);
+    if (rc != SDL_OK) return rc;
     return run_single_span<kFused>(a, n, fmt, vec, stream);
 }
 
@@ -1119,15 +1128,17 @@ int sdl_plan_message_bytes(const sdl_plan_t* plan, uint32_t p, sdl_format_t fmt,
 
 static int fused_fragment(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
                           const void* const* w_send_base, void* const* w_now_base, uint32_t M,
-                          sdl_format_t fmt, float lr, float mu, float alpha, void* stream, bool staged)
+                          sdl_format_t fmt, float lr, float mu, float alpha, void* const* codes_or_null,
+                          void* const* scales_or_null, void* stream, bool staged)
 {
     if (!plan || p >= sdl_plan_num_fragments(plan)) return SDL_ERR_INVALID_ARG;
-    // the whole-span scale needs scale words, which this call has no argument for: use the
-    // fragment-level send / receive calls (or the span-level fused call) instead
-    if (is_span_scaled(fmt)) return SDL_ERR_UNSUPPORTED;
+    // the whole-span scale needs scale words as workspace: only the calls that take them support it
+    if (valid_format(fmt) && is_span_scaled(fmt) && !scales_or_null) return SDL_ERR_UNSUPPORTED;
     Args a;
     bool vec = false;
     int rc = fill_fused_args(a, g_base, mom_base, w_send_base, w_now_base, M, fmt, lr, mu, alpha, &vec);
+    if (rc != SDL_OK) return rc;
+    rc = attach_fused_messages(a, M, fmt, codes_or_null, scales_or_null, &vec);
     if (rc != SDL_OK) return rc;
     a.staged = staged ? 1u : 0u;
     return launch_fragment<kFused>(a, plan, p, vec, fmt, stream);
@@ -1223,7 +1234,16 @@ int sdl_fragment_outer_step_plan(const sdl_plan_t* plan, uint32_t p, float* g_ba
                                  const void* const* w_send_base, void* const* w_now_base, uint32_t M,
                                  sdl_format_t fmt, float lr, float mu, float alpha, void* stream)
 {
-    return fused_fragment(plan, p, g_base, mom_base, w_send_base, w_now_base, M, fmt, lr, mu, alpha, stream, false);
+    return fused_fragment(plan, p, g_base, mom_base, w_send_base, w_now_base, M, fmt, lr, mu, alpha, nullptr, nullptr,
+                          stream, false);
+}
+int sdl_fragment_outer_step_plan_ex(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
+                                    const void* const* w_send_base, void* const* w_now_base, uint32_t M,
+                                    sdl_format_t fmt, float lr, float mu, float alpha, void* const* codes_or_null,
+                                    void* const* scales_or_null, void* stream)
+{
+    return fused_fragment(plan, p, g_base, mom_base, w_send_base, w_now_base, M, fmt, lr, mu, alpha, codes_or_null,
+                          scales_or_null, stream, false);
 }
 int sdl_quantize_outer_grad_plan(const sdl_plan_t* plan, uint32_t p, const float* g_base,
                                  const void* const* w_send_base, uint32_t M, sdl_format_t fmt,
@@ -1269,7 +1289,16 @@ int sdl_fragment_outer_step_staged(const sdl_plan_t* plan, uint32_t p, float* g_
                                    const void* const* w_send_base, void* const* w_now_base, uint32_t M,
                                    sdl_format_t fmt, float lr, float mu, float alpha, void* stream)
 {
-    return fused_fragment(plan, p, g_frag, mom_frag, w_send_base, w_now_base, M, fmt, lr, mu, alpha, stream, true);
+    return fused_fragment(plan, p, g_frag, mom_frag, w_send_base, w_now_base, M, fmt, lr, mu, alpha, nullptr, nullptr,
+                          stream, true);
+}
+int sdl_fragment_outer_step_staged_ex(const sdl_plan_t* plan, uint32_t p, float* g_frag, float* mom_frag,
+                                      const void* const* w_send_base, void* const* w_now_base, uint32_t M,
+                                      sdl_format_t fmt, float lr, float mu, float alpha, void* const* codes_or_null,
+                                      void* const* scales_or_null, void* stream)
+{
+    return fused_fragment(plan, p, g_frag, mom_frag, w_send_base, w_now_base, M, fmt, lr, mu, alpha, codes_or_null,
+                          scales_or_null, stream, true);
 }
 int sdl_quantize_outer_grad_staged(const sdl_plan_t* plan, uint32_t p, const float* g_frag,
                                    const void* const* w_send_base, uint32_t M, sdl_format_t fmt,

@@ -105,7 +105,54 @@ def test_fragment_level_calls_match_span_level_calls():
         assert torch.equal(a.view(torch.int16), b.view(torch.int16))
 
 
+@pytest.mark.parametrize("fmt", [sdl.FMT_E3M0, sdl.FMT_E4M3, sdl.FMT_E3M0_B128, sdl.FMT_E3M0_SPAN])
+@pytest.mark.parametrize("tau", [0, 1])
+def test_fused_fragment_call_with_messages(fmt, tau):
+    """The fused call of a whole fragment, messages written out: the messages are those of the
+    fragment-level send side, the state that of the three fragment-level calls; also for the
+    whole-span scale, whose scale words the call needs as workspace."""
+    numel, block, L = _small_model(seed=2)
+    P, M = 2, 3
+    plan = sdl.sdl_fragment_plan(numel, block, L, P, sdl.PATTERN_STRIDED, 10, tau)
+    total = plan.total_numel
+    g, mom, w_send, w_now = workloads.make_span(total, M, tau=tau, delta="student_t3", device=DEV)
+    g2, mom2 = g.clone(), mom.clone()
+    ws2 = [x.clone() for x in w_send]
+    wn2 = ws2 if tau == 0 else [x.clone() for x in w_now]
+    g3, mom3 = g.clone(), mom.clone()
+    ws3 = [x.clone() for x in w_send]
+    wn3 = ws3 if tau == 0 else [x.clone() for x in w_now]
+    for p in range(P):
+        cb, sb = sdl.sdl_plan_message_bytes(plan, p, fmt)
+        codes = [torch.zeros(cb, dtype=torch.uint8, device=DEV) for _ in range(M)]
+        scales = [torch.zeros(max(sb, 4), dtype=torch.uint8, device=DEV) for _ in range(M)]
+        sdl.sdl_fragment_outer_step_plan_ex(plan, p, g, mom, w_send, w_now, fmt, 0.7, 0.9, 0.5, codes, scales)
+        codes2 = [torch.zeros(cb, dtype=torch.uint8, device=DEV) for _ in range(M)]
+        scales2 = [torch.zeros(max(sb, 4), dtype=torch.uint8, device=DEV) for _ in range(M)]
+        sdl.sdl_quantize_outer_grad_plan(plan, p, g2, ws2, fmt, codes2, scales2)
+        sdl.sdl_dequant_reduce_nesterov_plan(plan, p, g2, mom2, codes2, scales2, fmt, 0.7, 0.9)
+        sdl.sdl_merge_overlap_plan(plan, p, g2, wn2, 0.5)
+        # without messages: scale words only where the format needs them as workspace
+        work = [torch.zeros(max(sb, 4), dtype=torch.uint8, device=DEV) for _ in range(M)]
+        sdl.sdl_fragment_outer_step_plan_ex(plan, p, g3, mom3, ws3, wn3, fmt, 0.7, 0.9, 0.5, None,
+                                            work if fmt == sdl.FMT_E3M0_SPAN else None)
+        torch.cuda.synchronize()
+        for m in range(M):
+            assert torch.equal(codes[m], codes2[m]), f"fragment {p} codes[{m}]"
+            assert torch.equal(scales[m][:sb], scales2[m][:sb]), f"fragment {p} scales[{m}]"
+    for a, b, what in ((g, g2, "g"), (mom, mom2, "mom"), (g3, g2, "g, no messages"), (mom3, mom2, "mom, no messages")):
+        assert torch.equal(a.view(torch.int32), b.view(torch.int32)), what
+    for a, b, c in zip(w_now, wn2, wn3):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+        assert torch.equal(c.view(torch.int16), b.view(torch.int16))
+    if fmt == sdl.FMT_E3M0_SPAN:
+        with pytest.raises(sdl.SdlError) as e:
+            sdl.sdl_fragment_outer_step_plan(plan, 0, g, mom, w_send, w_now, fmt, 0.7, 0.9, 0.5)
+        assert e.value.status == -2
+
+
 @pytest.mark.parametrize("taus,P,fmt,n_slots,lookahead", [
+    ((0, 0), 2, sdl.FMT_E3M0_SPAN, 1, 1),     # whole-span scale without overlap: staged fused call
     ((1, 1), 3, sdl.FMT_E3M0, 3, 1),          # the paper's setting, everything prefetched one step ahead
     ((0, 0), 3, sdl.FMT_E3M0, 1, 0),          # no overlap, a single slot, fetched on demand
     ((5, 5, 5, 5), 4, sdl.FMT_E3M0, 4, 2),    # several fragments in flight at once
