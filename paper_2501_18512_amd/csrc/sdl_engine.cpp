@@ -73,10 +73,10 @@ int sdl_engine_create(const sdl_plan_t* plan, uint32_t H, uint32_t M, const uint
 
 void sdl_engine_destroy(sdl_engine_t* e) { delete e; }
 
-int sdl_engine_bind(sdl_engine_t* e, float* g_base, float* mom_base, void* const* w_base, void* const* codes,
-                    void* const* scales)
+// The part of binding that does not depend on where the outer state lives.
+static int bind_replicas_and_messages(sdl_engine* e, void* const* w_base, void* const* codes, void* const* scales)
 {
-    if (!e || !g_base || !mom_base || !w_base) return SDL_ERR_INVALID_ARG;
+    if (!w_base) return SDL_ERR_INVALID_ARG;
     // without any delay the fused call is used, which keeps the messages in registers; the
     // whole-span scale still needs its scale words (as workspace)
     const bool need_codes = e->delay_max > 0;
@@ -87,12 +87,22 @@ int sdl_engine_bind(sdl_engine_t* e, float* g_base, float* mom_base, void* const
         if (!w_base[m]) return SDL_ERR_INVALID_ARG;
     for (size_t i = 0; i < (size_t)e->P * e->M; ++i)
         if ((need_codes && !codes[i]) || (need_scales && !scales[i])) return SDL_ERR_INVALID_ARG;
-    e->g = g_base; e->mom = mom_base;
     for (uint32_t m = 0; m < e->M; ++m) e->w[m] = w_base[m];
     for (size_t i = 0; i < (size_t)e->P * e->M; ++i) {
         e->codes[i] = need_codes ? codes[i] : nullptr;
         e->scales[i] = need_scales ? scales[i] : nullptr;
     }
+    return SDL_OK;
+}
+
+int sdl_engine_bind(sdl_engine_t* e, float* g_base, float* mom_base, void* const* w_base, void* const* codes,
+                    void* const* scales)
+{
+    if (!e || !g_base || !mom_base) return SDL_ERR_INVALID_ARG;
+    int rc = bind_replicas_and_messages(e, w_base, codes, scales);
+    if (rc != SDL_OK) return rc;
+    e->g = g_base; e->mom = mom_base;
+    e->offload = nullptr;
     e->bound = true;
     return SDL_OK;
 }
@@ -101,14 +111,13 @@ int sdl_engine_bind_offload(sdl_engine_t* e, sdl_offload_t* offload, void* const
                             void* const* scales, void* copy_stream, uint32_t lookahead)
 {
     if (!e || !offload) return SDL_ERR_INVALID_ARG;
-    // the flat g / mom pointers are never dereferenced in this mode: a non-null placeholder
-    static float placeholder;
-    int rc = sdl_engine_bind(e, &placeholder, &placeholder, w_base, codes, scales);
+    int rc = bind_replicas_and_messages(e, w_base, codes, scales);
     if (rc != SDL_OK) return rc;
-    e->g = e->mom = nullptr;
+    e->g = e->mom = nullptr;          // the outer state is reached through the staging pool only
     e->offload = offload;
     e->copy_stream = copy_stream;
     e->lookahead = lookahead;
+    e->bound = true;
     return SDL_OK;
 }
 
