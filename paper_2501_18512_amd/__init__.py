@@ -40,7 +40,7 @@ class _Span(ctypes.Structure):
 
 def _load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
-        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2501_18512_amd.build` "
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python paper_2501_18512_amd/build.py` "
                           "(there is no fallback path)")
     lib = ctypes.CDLL(LIB_PATH)
     vp, u32, u64, f32 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_float
