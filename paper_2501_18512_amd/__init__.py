@@ -5,7 +5,7 @@ point declared in include/sdl.h, takes torch tensors (device memory) where the C
 takes device pointers, and raises SdlError on a non-zero status.  All arithmetic runs
 in the HIP kernels of the library; there is no Python or CPU fallback, and importing
 this module fails loudly if the library has not been built
-(``python -m paper_2501_18512_amd.build``).
+(``python paper_2501_18512_amd/build.py``).
 """
 from __future__ import annotations
 
