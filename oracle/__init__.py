@@ -18,7 +18,7 @@ from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 
-from . import cosine  # noqa: F401
+from . import cosine, evalparams  # noqa: F401
 from .plan import (PATTERN_SEQUENTIAL, PATTERN_STRIDED, UNIT_POST, UNIT_PRE,  # noqa: F401
                    RefPlan, fragment_plan)
 
