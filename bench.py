@@ -234,6 +234,10 @@ def extras(st, fmt, wl, M, torch, sdl, args):
     dst = torch.empty_like(src)
     t = time_gpu(torch, lambda: sdl.sdl_copy_bytes(dst, src, nbytes), steps, warm)
     res["copy_kernel"] = {"ms": t, "GB/s": 2 * nbytes / t / 1e6, "bytes": nbytes}
+    # parameters handed to evaluation: fp32 mean of the replicas, written as bf16 (2M + 2 bytes per parameter)
+    ev = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    t = time_gpu(torch, lambda: sdl.sdl_evaluation_params(sdl.EVAL_REPLICA_MEAN, None, ws, n, ev), steps, warm)
+    res["evaluation_params_replica_mean"] = {"ms": t, "GB/s": (2 * M + 2) * n / t / 1e6}
     # diagnostics: cosine similarity of the replicas' outer gradients, per span and for the whole fragment
     # (reads 4 + 2M bytes per parameter)
     frag = st.fragment

@@ -378,6 +378,24 @@ int sdl_outer_grad_cosine_plan(const sdl_plan_t* plan, uint32_t p, const float* 
 int sdl_cosine_combine(const double* results, uint64_t stride_doubles, uint32_t n_sets, uint32_t M, double* result,
                        void* stream);
 
+/* ---- Parameters handed to evaluation -------------------------------------------------
+ *
+ * Appendix, paragraph "Which parameters to evaluate": the first replica, the average of all
+ * replicas, or the outer parameters (whose fragments were synchronised at different steps).
+ * out_bf16[i], in the model's storage type, is
+ *     SDL_EVAL_FIRST_REPLICA   w[0][i]
+ *     SDL_EVAL_REPLICA_MEAN    bf16( (((0 + float(w[0][i])) + float(w[1][i])) + ...) / float(M) ), fp32, RNE
+ *     SDL_EVAL_OUTER           bf16( g[i] ), RNE
+ * g (device, fp32) is only read for SDL_EVAL_OUTER and may be NULL otherwise; w (host array of
+ * M device pointers, bf16) is only read for the other two and may be NULL for SDL_EVAL_OUTER.
+ * out_bf16: device memory, numel bf16 values, owned by the caller; it must not overlap an input
+ * it is not identical to.  Any numel and 2-/4-byte alignment; 16-byte aligned arrays take the fast
+ * path.  Errors: SDL_ERR_INVALID_ARG (bad selector, M out of range, missing pointer),
+ * SDL_ERR_ALIGNMENT, SDL_ERR_UNSUPPORTED (numel above 2^40), SDL_ERR_DEVICE. */
+typedef enum { SDL_EVAL_FIRST_REPLICA = 0, SDL_EVAL_REPLICA_MEAN = 1, SDL_EVAL_OUTER = 2 } sdl_eval_params_t;
+int sdl_evaluation_params(sdl_eval_params_t which, const float* g, const void* const* w, uint32_t M, uint64_t numel,
+                          void* out_bf16, void* stream);
+
 /* Plain device-to-device streaming copy of nbytes (a multiple of 16; both pointers
  * 16-byte aligned).  Not part of the method: it is the yardstick against which the
  * achieved memory bandwidth of the calls above is judged (2 * nbytes of traffic). */

@@ -106,6 +106,7 @@ def _load() -> ctypes.CDLL:
     lib.sdl_offload_flush.argtypes = [vp, vp, vp]
     lib.sdl_engine_bind_offload.argtypes = [vp, vp, pp, pp, pp, vp, u32]
     lib.sdl_copy_bytes.argtypes = [vp, vp, u64, vp]
+    lib.sdl_evaluation_params.argtypes = [ctypes.c_int, vp, pp, u32, u64, vp, vp]
     lib.sdl_cosine_workspace_bytes.argtypes = [u32, u32]
     lib.sdl_cosine_workspace_bytes.restype = ctypes.c_size_t
     lib.sdl_outer_grad_cosine.argtypes = [vp, pp, u32, u64, vp, vp, ctypes.c_size_t, vp]
@@ -499,6 +500,15 @@ def sdl_engine_bind_offload(engine: Engine, pool: Offload, w_base, codes=None, s
 def sdl_copy_bytes(dst, src, nbytes: int, stream=None):
     _require_device(dst, src)
     _check(_lib.sdl_copy_bytes(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "sdl_copy_bytes")
+
+
+EVAL_FIRST_REPLICA, EVAL_REPLICA_MEAN, EVAL_OUTER = 0, 1, 2
+
+
+def sdl_evaluation_params(which: int, g, w, n: int, out_bf16, stream=None):
+    _require_device(g, *(w or []), out_bf16)
+    _check(_lib.sdl_evaluation_params(which, _ptr(g), _ptr_array(w), len(w) if w else 0, n, _ptr(out_bf16),
+                                      _stream(stream)), "sdl_evaluation_params")
 
 
 def sdl_cosine_workspace_bytes(M: int, n_sets: int) -> int:

@@ -7,7 +7,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = [os.path.join(HERE, "csrc", f) for f in ("sdl_kernels.hip", "sdl_cosine.hip", "sdl_plan.cpp", "sdl_engine.cpp",
+SOURCES = [os.path.join(HERE, "csrc", f) for f in ("sdl_kernels.hip", "sdl_cosine.hip", "sdl_eval.hip", "sdl_plan.cpp", "sdl_engine.cpp",
                                                    "sdl_offload.cpp")]
 LIB = os.path.join(HERE, "libsdl.so")
 
