@@ -60,15 +60,18 @@ def test_mean_may_overwrite_the_first_replica():
 
 
 def test_special_values():
-    g = torch.tensor([float("inf"), -float("inf"), float("nan"), 3.3961775e38, 1.00390625, 1.01171875, -0.0, 1e-40],
-                     dtype=torch.float32, device=DEV)
-    out = torch.zeros(8, dtype=torch.bfloat16, device=DEV)
-    sdl.sdl_evaluation_params(sdl.EVAL_OUTER, g, None, 8, out)
+    bits = np.array([0x7f800000, 0xff800000, 0x7fc00000, 0x7f7f8000, 0x3f808000, 0x3f818000, 0x80000000, 0x00011704,
+                     0x7f800001, 0xff80ffff], np.uint32)       # the last two: NaN with payload only in the low half
+    g = torch.from_numpy(bits.view(np.float32)).to(DEV)
+    n = bits.size
+    out = torch.zeros(n, dtype=torch.bfloat16, device=DEV)
+    sdl.sdl_evaluation_params(sdl.EVAL_OUTER, g, None, n, out)
     torch.cuda.synchronize()
     got, want = host_bits(out), ref.evaluation_params(ref.OUTER, host_f32(g), [])
-    nan = np.array([False, False, True, False, False, False, False, False])
+    nan = np.isnan(bits.view(np.float32))
+    assert nan.sum() == 3
     assert np.array_equal(got[~nan], want[~nan])
-    assert (got[2] & 0x7f80) == 0x7f80 and (got[2] & 0x7f) != 0
+    assert np.all((got[nan] & 0x7f80) == 0x7f80) and np.all((got[nan] & 0x7f) != 0)      # NaN stays NaN
 
 
 def test_argument_errors():

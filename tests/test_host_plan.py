@@ -198,3 +198,21 @@ def test_cosine_calls_reject_bad_arguments_before_launch():
     assert lib.sdl_cosine_combine(good, 8, 3, 2, good, 0) == -1                               # stride shorter than a result
     assert lib.sdl_cosine_combine(0, 9, 3, 2, good, 0) == -1
     assert lib.sdl_cosine_combine(good, 9, 3, 0, good, 0) == -1
+
+
+def test_evaluation_params_rejects_bad_arguments_before_launch():
+    lib, good = sdl._lib, 0x1000
+    ptrs = lambda xs: (ctypes.c_void_p * len(xs))(*xs)
+    call = lib.sdl_evaluation_params
+    assert call(3, good, ptrs([good]), 1, 64, good, 0) == -1                       # no such selector
+    assert call(sdl.EVAL_REPLICA_MEAN, good, ptrs([good]), 0, 64, good, 0) == -1   # M = 0
+    assert call(sdl.EVAL_REPLICA_MEAN, good, ptrs([good] * 17), 17, 64, good, 0) == -1
+    assert call(sdl.EVAL_REPLICA_MEAN, good, None, 2, 64, good, 0) == -1           # replicas missing
+    assert call(sdl.EVAL_REPLICA_MEAN, good, ptrs([good, 0]), 2, 64, good, 0) == -1
+    assert call(sdl.EVAL_OUTER, 0, None, 0, 64, good, 0) == -1                     # outer parameters missing
+    assert call(sdl.EVAL_OUTER, good, None, 0, 64, 0, 0) == -1                     # output missing
+    assert call(sdl.EVAL_OUTER, good + 2, None, 0, 64, good, 0) == -3
+    assert call(sdl.EVAL_FIRST_REPLICA, 0, ptrs([good + 1]), 1, 64, good, 0) == -3
+    assert call(sdl.EVAL_REPLICA_MEAN, 0, ptrs([good]), 1, 64, good + 1, 0) == -3
+    assert call(sdl.EVAL_OUTER, good, None, 0, (2 ** 31) * 512, good, 0) == -2     # beyond the supported size
+    assert call(sdl.EVAL_REPLICA_MEAN, 0, None, 2, 0, 0, 0) == 0                   # nothing to do

@@ -28,8 +28,10 @@ def test_bf16_rounding_against_torch_and_by_hand():
     assert ep.bf16_round(np.array([1.00390625], np.float32))[0] == 0x3f80          # tie to even: down
     assert ep.bf16_round(np.array([1.01171875], np.float32))[0] == 0x3f82          # tie to even: up
     assert ep.bf16_round(np.array([3.3961775e38], np.float32))[0] == 0x7f80        # rounds up to infinity
-    nan = ep.bf16_round(np.array([np.nan], np.float32))[0]
-    assert (nan & 0x7f80) == 0x7f80 and (nan & 0x7f) != 0
+    # NaN stays NaN, also one whose payload sits only in the bits that are rounded away
+    for pattern in (0x7fc00000, 0x7f800001, 0xff80ffff):
+        nan = ep.bf16_round(np.array([pattern], np.uint32).view(np.float32))[0]
+        assert (nan & 0x7f80) == 0x7f80 and (nan & 0x7f) != 0 and (nan >> 15) == (pattern >> 31)
 
 
 def test_three_candidates_on_a_hand_case():
