@@ -29,9 +29,13 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 DEFAULT_FRAGMENT = {"tiny": 0, "100m": 1, "1b": 1, "4b_p6": 1, "4b_p1": 0, "stress": 1}
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by
 # the reading of the copy kernel); see profiles/.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {
+MEASURED_TRAFFIC_BYTES = {     # (workload, M, format), default fragment of the workload
     # profiles/fused_e3m0_1b_m4_hbm_traffic.txt: 7.2478e9 B fetched + 4.8323e9 B written per launch
     ("1b", 4, "e3m0"): 12.0801e9,
+    # profiles/fused_e3m0_other_workloads_hbm_traffic.txt
+    ("stress", 8, "e3m0"): 19.3280e9,
+    ("4b_p6", 2, "e3m0"): 19.0254e9,
+    ("100m", 2, "e3m0"): 0.79297e9,
 }
 
 
@@ -159,7 +163,8 @@ def main() -> int:
         "roofline": {
             "bound": "hbm", "kernel": "sdl_kernel<fused>", "achieved": achieved, "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, M, fmt_name)),
+            "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, M, fmt_name))
+            if frag == DEFAULT_FRAGMENT[args.workload] else None,
             "algorithmic_bytes_per_param": bpp, "bytes_per_launch": bpp * st.n / n_launch,
             "launch_ms": launch_ms,
         },
