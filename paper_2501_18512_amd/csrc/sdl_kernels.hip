@@ -791,19 +791,22 @@ size_t code_bytes_at(sdl_format_t fmt, uint64_t elem)
 }
 
 // Dynamic LDS requested per workgroup.  The kernels use no LDS; the request only caps how
-// many wavefronts share a CU (160 KiB of LDS per CU), which is the knob that matters for a
-// streaming kernel: enough loads in flight, not so many that the access window in each
-// array grows and DRAM page locality is lost.  Measured on MI355X: the fused kernel with
-// a compile-time replica count is fastest at 8 wavefronts per CU (12 when w_send aliases
-// w_now), the one-pass receive kernel at 12; the other kernels want every wavefront they
-// can get.
+// many wavefronts share a CU (160 KiB of LDS per CU: 20480 B -> 8, 13653 B -> 12, 10240 B -> 16),
+// which is the knob that matters for a streaming kernel: enough loads in flight, not so many
+// that the access window in each array grows and DRAM page locality is lost.  Measured on
+// MI355X (medians of three runs over 302 M parameters, replica counts 2 / 4 / 8): the kernels
+// that write the replicas back want few wavefronts -- fused 8 (12 when w_send aliases w_now),
+// one-pass receive 8 / 12 / 8, merge 16 / 12 / 8 -- while the send side and the receive side
+// without the merge want every wavefront they can get.
 // SDL_TUNE_LDS_BYTES in the environment overrides the choice (tuning aid).
 uint32_t lds_cap_bytes(int mode, uint32_t mt, bool aliased)
 {
     static const int env = [] { const char* e = std::getenv("SDL_TUNE_LDS_BYTES"); return e ? std::atoi(e) : -1; }();
     if (env >= 0) return (uint32_t)env;
-    if (mode == kFused && mt > 0) return aliased ? 13653u : 20480u;
-    if (mode == kReceive && mt > 0) return 13653u;
+    if (mt == 0) return 0u;
+    if (mode == kFused) return aliased ? 13653u : 20480u;
+    if (mode == kReceive) return mt == 4 ? 13653u : 20480u;
+    if (mode == kMerge) return mt <= 2 ? 10240u : (mt == 4 ? 13653u : 20480u);
     return 0u;
 }
 
