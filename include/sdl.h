@@ -378,6 +378,18 @@ int sdl_outer_grad_cosine_plan(const sdl_plan_t* plan, uint32_t p, const float* 
 int sdl_cosine_combine(const double* results, uint64_t stride_doubles, uint32_t n_sets, uint32_t M, double* result,
                        void* stream);
 
+/* Cosine similarity inside the schedule driver: after this call, every send of fragment p
+ * first runs sdl_outer_grad_cosine_plan on the outer gradients that are about to be sent (the
+ * curves of the appendix are this, recorded over training).  fragment_results: device memory,
+ * P results of 2*M*M + 1 doubles, result p rewritten at every send of fragment p;
+ * span_results: NULL, or a host array of P device pointers (entries may be NULL) to
+ * n_spans(p) results each; workspace: device memory, at least the largest
+ * sdl_cosine_workspace_bytes(M, n_spans(p)) over the fragments, shared by all sends (they run
+ * on one stream).  fragment_results == NULL switches the diagnostics off.  Not available while
+ * the outer state is offloaded (sdl_engine_step then returns SDL_ERR_UNSUPPORTED). */
+int sdl_engine_track_cosine(sdl_engine_t* engine, double* const* span_results, double* fragment_results,
+                            void* workspace, size_t workspace_bytes);
+
 /* ---- Parameters handed to evaluation -------------------------------------------------
  *
  * Appendix, paragraph "Which parameters to evaluate": the first replica, the average of all

@@ -106,6 +106,7 @@ def _load() -> ctypes.CDLL:
     lib.sdl_offload_flush.argtypes = [vp, vp, vp]
     lib.sdl_engine_bind_offload.argtypes = [vp, vp, pp, pp, pp, vp, u32]
     lib.sdl_copy_bytes.argtypes = [vp, vp, u64, vp]
+    lib.sdl_engine_track_cosine.argtypes = [vp, pp, vp, vp, ctypes.c_size_t]
     lib.sdl_evaluation_params.argtypes = [ctypes.c_int, vp, pp, u32, u64, vp, vp]
     lib.sdl_cosine_workspace_bytes.argtypes = [u32, u32]
     lib.sdl_cosine_workspace_bytes.restype = ctypes.c_size_t
@@ -552,6 +553,15 @@ def sdl_cosine_combine(results, n_sets: int, M: int, result, stream=None, stride
     stride = cosine_result_doubles(M) if stride_doubles is None else stride_doubles
     _check(_lib.sdl_cosine_combine(_ptr(results), stride, n_sets, M, _ptr(result), _stream(stream)),
            "sdl_cosine_combine")
+
+
+def sdl_engine_track_cosine(engine: "Engine", span_results, fragment_results, workspace):
+    """span_results: None or a list of P tensors (or None entries); fragment_results: [P, 2*M*M+1] fp64."""
+    _require_device(fragment_results, workspace, *[t for t in (span_results or []) if t is not None])
+    _check(_lib.sdl_engine_track_cosine(engine._h, _ptr_array(span_results), _ptr(fragment_results), _ptr(workspace),
+                                        workspace.numel() if workspace is not None else 0),
+           "sdl_engine_track_cosine")
+    engine._keep_cosine = (span_results, fragment_results, workspace)
 
 
 def alloc_exchange(fmt: int, n: int, M: int, device="cuda"):

@@ -30,6 +30,12 @@ struct sdl_engine {
     std::vector<uint64_t> sent_at;
     std::vector<uint8_t> reduced;
     std::vector<uint8_t> merged;         // P*M
+    // optional diagnostics: cosine similarity of the outer gradients at every send
+    bool track_cosine = false;
+    std::vector<double*> cos_span_results;   // per fragment, may hold null pointers
+    double* cos_fragment_results = nullptr;  // [P][2*M*M + 1]
+    void* cos_workspace = nullptr;
+    size_t cos_workspace_bytes = 0;
 };
 
 extern "C" {
@@ -121,6 +127,38 @@ int sdl_engine_bind_offload(sdl_engine_t* e, sdl_offload_t* offload, void* const
     return SDL_OK;
 }
 
+int sdl_engine_track_cosine(sdl_engine_t* e, double* const* span_results, double* fragment_results, void* workspace,
+                            size_t workspace_bytes)
+{
+    if (!e) return SDL_ERR_INVALID_ARG;
+    if (!fragment_results) {             // switch the diagnostics off
+        e->track_cosine = false;
+        return SDL_OK;
+    }
+    if (!workspace) return SDL_ERR_INVALID_ARG;
+    size_t need = 0;
+    for (uint32_t p = 0; p < e->P; ++p) {
+        const sdl_span_t* spans = nullptr;
+        uint32_t n_spans = 0;
+        int rc = sdl_plan_fragment_spans(e->plan, p, &spans, &n_spans);
+        if (rc != SDL_OK) return rc;
+        const size_t bytes = sdl_cosine_workspace_bytes(e->M, n_spans);
+        if (bytes > need) need = bytes;
+    }
+    if (workspace_bytes < need) return SDL_ERR_INVALID_ARG;
+    try {
+        e->cos_span_results.assign(e->P, nullptr);
+    } catch (const std::bad_alloc&) {
+        return SDL_ERR_NOMEM;
+    }
+    for (uint32_t p = 0; p < e->P && span_results; ++p) e->cos_span_results[p] = span_results[p];
+    e->cos_fragment_results = fragment_results;
+    e->cos_workspace = workspace;
+    e->cos_workspace_bytes = workspace_bytes;
+    e->track_cosine = true;
+    return SDL_OK;
+}
+
 int sdl_engine_step(sdl_engine_t* e, uint64_t t, void* stream, uint32_t* n_sent, uint32_t* n_received)
 {
     if (!e || !e->bound || t == 0) return SDL_ERR_INVALID_ARG;
@@ -143,6 +181,14 @@ int sdl_engine_step(sdl_engine_t* e, uint64_t t, void* stream, uint32_t* n_sent,
         }
         if (sends) {
             if (e->sent_at[p] != 0) return SDL_ERR_INVALID_ARG;      // previous message not consumed: steps skipped
+            if (e->track_cosine) {
+                // the outer gradients that are about to be sent, before anything is updated
+                if (staged) return SDL_ERR_UNSUPPORTED;
+                int rc = sdl_outer_grad_cosine_plan(e->plan, p, g, e->w.data(), M, e->cos_span_results[p],
+                                                    e->cos_fragment_results + (size_t)p * SDL_COSINE_RESULT_DOUBLES(M),
+                                                    e->cos_workspace, e->cos_workspace_bytes, stream);
+                if (rc != SDL_OK) return rc;
+            }
             if (e->delay_max == 0) {
                 // no overlap anywhere: the whole outer step at once, messages kept in registers (the
                 // whole-span scale uses the fragment's scale words as workspace)

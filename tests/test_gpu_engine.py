@@ -208,6 +208,64 @@ def test_engine_with_outer_state_in_host_memory(taus, P, fmt, n_slots, lookahead
         assert_bf16_within_ulp(host_bits(w[m]), ref.w[m], f"offloaded w[{m}]")
 
 
+@pytest.mark.parametrize("taus", [(0, 0, 0), (2, 2, 2)])
+def test_engine_tracks_cosine_similarity_at_every_send(taus):
+    """Appendix: the similarity between the replicas' outer gradients, recorded when they are sent."""
+    from oracle import cosine as ref_cosine
+    H, M, P = 8, len(taus), 3
+    numel, block, L = _small_model(seed=3)
+    plan = sdl.sdl_fragment_plan(numel, block, L, P, sdl.PATTERN_STRIDED, H, min(taus))
+    total = plan.total_numel
+    g, mom, w, _ = workloads.make_span(total, M, tau=0, delta="shared10", device=DEV)
+    eng = sdl.sdl_engine_create(plan, H, taus, sdl.FMT_E3M0, 0.7, 0.9, 0.5)
+    codes, scales = [], []
+    for p in range(P):
+        cb, sb = sdl.sdl_plan_message_bytes(plan, p, sdl.FMT_E3M0)
+        for m in range(M):
+            codes.append(torch.zeros(max(cb, 16), dtype=torch.uint8, device=DEV))
+            scales.append(torch.zeros(max(sb, 16), dtype=torch.uint8, device=DEV))
+    sdl.sdl_engine_bind(eng, g, mom, w, codes, scales)
+    R = sdl.cosine_result_doubles(M)
+    spans = [sdl.sdl_plan_fragment_spans(plan, p) for p in range(P)]
+    frag_results = torch.full((P, R), float("nan"), dtype=torch.float64, device=DEV)
+    span_results = [torch.full((len(spans[p]), R), float("nan"), dtype=torch.float64, device=DEV) if p != 1 else None
+                    for p in range(P)]
+    work = torch.empty(max(sdl.sdl_cosine_workspace_bytes(M, len(sp)) for sp in spans), dtype=torch.uint8, device=DEV)
+    with pytest.raises(sdl.SdlError):
+        sdl.sdl_engine_track_cosine(eng, span_results, frag_results, work[:1024])
+    sdl.sdl_engine_track_cosine(eng, span_results, frag_results, work)
+    gen = torch.Generator(DEV).manual_seed(11)
+    checked = 0
+    for t in range(1, 3 * H + 1):
+        for m in range(M):
+            w[m].copy_((w[m].float() + torch.randn(total, device=DEV, generator=gen) * 3e-4).bfloat16())
+        sending = sdl.sdl_plan_events(plan, t)[0]
+        hg, hw = host_f32(g), [host_bits(x) for x in w]          # the state the sends of this step see
+        sdl.sdl_engine_step(eng, t)
+        torch.cuda.synchronize()
+        for p in sending:
+            grams = []
+            for i, (off, n, _) in enumerate(spans[p]):
+                G, cos, mean = ref_cosine.outer_grad_cosine(hg[off:off + n], [x[off:off + n] for x in hw])
+                grams.append(G)
+                if span_results[p] is not None:
+                    got = sdl.split_cosine_result(span_results[p][i], M)
+                    assert np.all(np.abs(got[1].cpu().numpy() - cos) <= 1e-11)
+            G, cos, mean = ref_cosine.combine(grams)
+            got_G, got_cos, got_mean = (x.cpu().numpy() for x in sdl.split_cosine_result(frag_results[p], M))
+            assert np.all(np.abs(got_G - G) <= 1e-11 * np.sqrt(np.outer(np.diag(G), np.diag(G))))
+            assert np.all(np.abs(got_cos - cos) <= 1e-11) and abs(float(got_mean) - mean) <= 1e-11
+            checked += 1
+    assert checked == 2 * P + sum(1 for p in range(P) if sdl.sdl_plan_offset(plan, p) == 0)
+    # switched off again: nothing is written any more
+    sdl.sdl_engine_track_cosine(eng, None, None, None)
+    frag_results.fill_(7.0)
+    for t in range(3 * H + 1, 4 * H + 1):
+        sdl.sdl_engine_step(eng, t)
+    torch.cuda.synchronize()
+    assert torch.all(frag_results == 7.0)
+
+
 def test_fragment_step_can_be_captured_in_a_graph():
     """The calls only enqueue kernels (no allocation, no synchronisation, no memset node), so a
     caller may capture them in a HIP graph.  Three replays, with eager work and synchronisations

@@ -166,6 +166,14 @@ def test_engine_rejects_bad_arguments():
         sdl.sdl_engine_step(eng, 1, stream=0)                                        # not bound
     with pytest.raises(sdl.SdlError):
         sdl.sdl_engine_bind(eng, 0x1000, 0x1000, [0x1000, 0x1000], None, None)      # overlap needs message buffers
+    # cosine tracking: host-side checks only (nothing is launched before a step)
+    lib = sdl._lib
+    need = sdl.sdl_cosine_workspace_bytes(2, 2)
+    assert lib.sdl_engine_track_cosine(eng._h, None, 0x1000, 0x1000, need - 1) == -1      # workspace too small
+    assert lib.sdl_engine_track_cosine(eng._h, None, 0x1000, None, need) == -1            # workspace missing
+    assert lib.sdl_engine_track_cosine(None, None, 0x1000, 0x1000, need) == -1
+    assert lib.sdl_engine_track_cosine(eng._h, None, 0x1000, 0x1000, need) == 0
+    assert lib.sdl_engine_track_cosine(eng._h, None, None, None, 0) == 0                   # off again
     assert sdl.sdl_plan_message_bytes(plan, 0, sdl.FMT_E3M0) == (2 * 512 // 2, 2 * 512 // 32)
     assert sdl.sdl_plan_message_bytes(plan, 0, sdl.FMT_E3M0_B128) == (2 * 512 // 2, 2 * 512 // 128)
     assert sdl.sdl_plan_message_bytes(plan, 0, sdl.FMT_E3M0_SPAN) == (2 * 512 // 2, 2 * 4)
