@@ -1,6 +1,8 @@
 """Seeded random sweep of the span-level calls against the oracle: format, replica count, size,
 element offsets of every array (so that 16-byte alignment comes and goes independently per
 array), hyper-parameters, delta distribution, aliasing and whether messages are written."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -52,7 +54,11 @@ def _make(c):
     return g, mom, w_send, w_now
 
 
-@pytest.mark.parametrize("chunk", range(8))
+# more seeds on request (a soak of the same sweep): SDL_TEST_RANDOM_CHUNKS=100 python -m pytest ...
+N_CHUNKS = int(os.environ.get("SDL_TEST_RANDOM_CHUNKS", "8"))
+
+
+@pytest.mark.parametrize("chunk", range(N_CHUNKS))
 def test_random_fused_and_unfused_cases(chunk):
     rng = np.random.default_rng(1000 + chunk)
     for i in range(24):
