@@ -12,8 +12,10 @@
  *
  * and sdl_fragment_plan builds the fragment map and the send/receive schedule on
  * the host; the *_plan forms of the calls work on whole fragments of a plan, and
- * sdl_engine_step drives them along the schedule.  The M replicas ("workers") are M parameter arrays resident in one
- * GPU's memory; no call communicates with another device.
+ * sdl_engine_step drives them along the schedule.  sdl_offload_* keep the outer state
+ * in host memory; sdl_outer_grad_cosine* and sdl_evaluation_params are the appendix's
+ * diagnostics on the same arrays.  The M replicas ("workers") are M parameter arrays
+ * resident in one GPU's memory; no call communicates with another device.
  *
  * Conventions for every call
  *   - Returns an sdl_status_t (0 = SDL_OK, negative = error).  Never throws, never
