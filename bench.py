@@ -102,6 +102,8 @@ def main() -> int:
                     help="also time the receive side and the fused step over M in {1,2,4,8} x {e3m0,e4m3,bf16}")
     ap.add_argument("--offload", action="store_true",
                     help="also time the fragment step with g / mom staged from pinned host memory")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the same steps replayed from one captured HIP graph (launch-bound small cases)")
     ap.add_argument("--engine", action="store_true",
                     help="also walk the schedule driver over whole outer rounds (all P fragments, messages in HBM)")
     args = ap.parse_args()
@@ -176,6 +178,8 @@ def main() -> int:
         out["sweep"] = sweep(st, frag, wl, M, torch, sdl, args)
     if args.offload:
         out["offload"] = offload_timing(st, frag, fmt, wl, M, torch, sdl, args)
+    if args.graph:
+        out["graph"] = graph_timing(step, st, bpp, torch, args)
     if args.engine:
         out["engine"] = engine_timing(st, fmt, wl, M, torch, sdl, workloads)
     print(json.dumps(out))
@@ -312,6 +316,35 @@ def offload_timing(st, frag, fmt, wl, M, torch, sdl, args):
         res[name] = {"ms": ms, "GB/s": (8 * st.n if name != "staged_step" else
                                         algorithmic_bytes_per_param(M, wl.tau) * st.n) / ms / 1e6}
     return res
+
+
+def graph_timing(step, st, bpp, torch, args):
+    """The timed loop once more, as one captured graph of `steps` launches replayed from the host with a
+    single call: what is left of the per-step time when the launch overhead is taken out (the calls
+    allocate nothing and use no memset, so they can be captured as they are)."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for _ in range(args.steps):
+            step()
+    for _ in range(2):
+        graph.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 5
+    e0.record()
+    for _ in range(reps):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / (reps * args.steps)
+    return {"ms_per_step": ms, "params_per_s": st.n / (ms * 1e-3), "GB/s": bpp * st.n / ms / 1e6,
+            "steps_per_graph": args.steps}
 
 
 def engine_timing(st, fmt, wl, M, torch, sdl, workloads):
