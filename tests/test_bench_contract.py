@@ -42,3 +42,11 @@ def test_one_json_line_with_roofline_and_cpu_baseline(workload):
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["unit"] == "params/s" and c["value"] > 0 and 1 <= c["cores"] <= 16
     assert isinstance(c["sample"], str) and c["single_thread"]["cores"] == 1
+
+
+@pytest.mark.gpu
+def test_smoke_entry_point():
+    if ROOT not in sys.path:
+        sys.path.insert(0, ROOT)
+    import __graft_entry__
+    __graft_entry__.smoke()
