@@ -1,7 +1,8 @@
 """CPU oracle of the Streaming DiLoCo fragment outer step (TEST INFRASTRUCTURE ONLY).
 
-Thin numpy/ctypes front end of ``sdl_ref.c`` (arithmetic) and ``plan.py``
-(fragment map and schedule).  Nothing in the GPU package may import this
+Thin numpy/ctypes front end of ``sdl_ref.c`` (arithmetic of the outer step) and ``plan.py``
+(fragment map and schedule); ``engine.py`` walks Algorithm 2 over many steps with them;
+``cosine.py`` and ``evalparams.py`` are the appendix's diagnostics, in numpy.  Nothing in the GPU package may import this
 package; only the tests, the smoke check and the CPU-baseline leg of the
 benchmark do.  The C file is compiled with gcc, ``-O2 -ffp-contract=off`` so
 that every fp32 operation rounds once, as written.
