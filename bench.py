@@ -94,7 +94,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="1b", choices=sorted(DEFAULT_FRAGMENT))
     ap.add_argument("--fragment", type=int, default=None)
-    ap.add_argument("--format", default=None, choices=["e3m0", "e4m3", "bf16", "fp32"])
+    ap.add_argument("--format", default=None,
+                    choices=["e3m0", "e4m3", "bf16", "fp32", "e3m0_b64", "e3m0_b128", "e3m0_span"])
     ap.add_argument("--workers", type=int, default=None, help="override M")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the unfused / copy side measurements")
@@ -133,13 +134,26 @@ def main() -> int:
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(st, fmt, torch, workloads)
 
+    # the whole-span scale needs its scale words (one per span and replica) as workspace
+    span_words = None
+    if fmt == sdl.FMT_E3M0_SPAN:
+        span_words = [torch.zeros(max(sdl.sdl_plan_message_bytes(st.plan, frag, fmt)[1], 4), dtype=torch.uint8,
+                                  device="cuda") for _ in range(M)]
+
     def step():
-        sdl.sdl_fragment_outer_step_plan(st.plan, frag, st.g, st.mom, st.w_send, st.w_now, fmt, wl.lr, wl.mu,
-                                         wl.alpha)
+        sdl.sdl_fragment_outer_step_plan_ex(st.plan, frag, st.g, st.mom, st.w_send, st.w_now, fmt, wl.lr, wl.mu,
+                                            wl.alpha, None, span_words)
 
     n_launch = -(-len(st.runs) // 16)
     ms = time_gpu(torch, step, args.steps, args.warmup)
     bpp = algorithmic_bytes_per_param(M, wl.tau)
+    kernel_name = "sdl_kernel<fused>"
+    if fmt == sdl.FMT_E3M0_SPAN:
+        # one scale per span: an extra read pass over g and w_send for the grid-wide maximum, and one
+        # launch group per 16 spans; the step is reported as a whole
+        bpp += 4.0 + 2.0 * M
+        n_launch = 1
+        kernel_name = "sdl_kernel<absmax> + sdl_kernel<fused>, all launches of the step"
     launch_ms = ms / n_launch
     achieved = bpp * st.n / n_launch / (launch_ms * 1e-3) / 1e9
     out = {
@@ -163,7 +177,7 @@ def main() -> int:
             "launches_per_step": n_launch,
         },
         "roofline": {
-            "bound": "hbm", "kernel": "sdl_kernel<fused>", "achieved": achieved, "peak": HBM_PEAK_GBS,
+            "bound": "hbm", "kernel": kernel_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, M, fmt_name))
             if frag == DEFAULT_FRAGMENT[args.workload] else None,

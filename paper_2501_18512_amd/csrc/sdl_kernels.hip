@@ -41,7 +41,7 @@ constexpr int kRow = kVec * kWave;            // parameters per row (256)
 constexpr int kGroup = kRow * kRows;          // parameters per workgroup tile (512)
 constexpr int kMaxRuns = 16;                  // runs per launch
 
-enum Mode { kQuantize = 0, kReduce = 1, kMerge = 2, kFused = 3, kAbsmax = 4, kReceive = 5 };   // kReceive = kReduce + kMerge
+enum Mode { kQuantize = 0, kReduce = 1, kMerge = 2, kFused = 3, kReceive = 5 };   // kReceive = kReduce + kMerge
 
 constexpr bool is_e3m0(int f) { return f == SDL_FMT_E3M0 || f >= SDL_FMT_E3M0_B64; }
 constexpr bool is_scaled(int f) { return f == SDL_FMT_E4M3 || is_e3m0(f); }
@@ -317,13 +317,6 @@ struct TileIO {
     {
         return reinterpret_cast<const uint32_t*>(a.scales[m])[sidx];
     }
-    // fold a wavefront's maximum into the span's scale word
-    __device__ __forceinline__ void span_amax_update(uint32_t m, uint32_t v) const
-    {
-        uint32_t* p = reinterpret_cast<uint32_t*>(a.scales[m]) + sidx;
-        if (v > __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
-            __hip_atomic_fetch_max(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
     template <int FMT> __device__ __forceinline__ float load_scale(uint32_t m, int row) const
     {
         if constexpr (is_span_scaled(FMT)) {
@@ -442,13 +435,6 @@ struct GuardedIO {
     __device__ __forceinline__ uint32_t span_amax(uint32_t m) const
     {
         return reinterpret_cast<const uint32_t*>(a.scales[m])[sidx];
-    }
-    // fold a wavefront's maximum into the span's scale word
-    __device__ __forceinline__ void span_amax_update(uint32_t m, uint32_t v) const
-    {
-        uint32_t* p = reinterpret_cast<uint32_t*>(a.scales[m]) + sidx;
-        if (v > __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
-            __hip_atomic_fetch_max(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 
     // lane's first element of a row, counted from the run start, and how many of its 4 exist
@@ -585,7 +571,7 @@ __device__ __forceinline__ void process(const Args& a, const IO& io)
         if constexpr (MODE == kReduce || MODE == kFused || MODE == kReceive) io.load_mom(r, mom[r]);
     }
     if constexpr (MT > 0) {
-        if constexpr (MODE == kQuantize || MODE == kFused || MODE == kAbsmax) {
+        if constexpr (MODE == kQuantize || MODE == kFused) {
 #pragma unroll
             for (int m = 0; m < MT; ++m)
 #pragma unroll
@@ -603,29 +589,6 @@ __device__ __forceinline__ void process(const Args& a, const IO& io)
 #pragma unroll
                 for (int r = 0; r < kRows; ++r) io.load_wn(m, r, wn[m][r]);
         }
-    }
-
-    // ---- pre-pass of the whole-span scale: absolute maximum of every replica's outer gradient
-    if constexpr (MODE == kAbsmax) {
-#pragma unroll
-        for (uint32_t m = 0; m < M; ++m) {
-            const int mi = MT > 0 ? (int)m : 0;
-            uint32_t amax = 0;
-#pragma unroll
-            for (int r = 0; r < kRows; ++r) {
-                if constexpr (MT == 0) io.load_ws(m, r, ws[0][r]);
-                float w[kVec];
-                unpack_bf16(ws[mi][r], w);
-#pragma unroll
-                for (int j = 0; j < kVec; ++j) {
-                    const uint32_t b = f2u(g[r][j] - w[j]) & 0x7fffffffu;
-                    amax = b > amax ? b : amax;
-                }
-            }
-            amax = lanes_max<kWave>(amax);
-            if (io.lane == 0u) io.span_amax_update(m, amax);
-        }
-        return;
     }
 
     // ---- outer gradients, messages, fp32 sum over replicas in ascending order
@@ -754,6 +717,108 @@ void sdl_kernel(const Args a)
     }
 }
 
+// Pre-pass of the whole-span scale: the absolute maximum of every replica's outer gradient over
+// each run of the launch, folded into the run's scale word with an integer atomic maximum (the
+// words hold fp32 bit patterns of non-negative values, which order like the values).  A fixed
+// number of workgroups is shared out among the runs; workgroup k of a run walks the run's tiles
+// k, k + G, ... with 8 consecutive parameters per lane (128-bit loads, the next tile's loads issued
+// before the current tile is consumed), keeps the running maxima in registers, and touches the
+// scale words once at the very end -- one atomic per workgroup and replica instead of one per tile,
+// which all landed on the same few cache lines.
+struct AbsmaxShare {
+    uint32_t first[kMaxRuns];     // first workgroup of run r in this launch
+    uint32_t G[kMaxRuns];         // workgroups of run r (>= 1)
+    uint32_t m0;                  // first replica handled by this launch
+};
+
+template <int MB>
+struct AbsmaxTile {
+    u32x4 g0, g1;
+    u32x4 w[MB];
+};
+
+template <int MB>
+__device__ __forceinline__ void absmax_load(AbsmaxTile<MB>& t, const Args& a, uint32_t m0, uint64_t ge, uint64_t we,
+                                            uint32_t valid, bool fast, uint32_t lane)
+{
+    if (fast && valid == (uint32_t)kGroup) {
+        const __amdgpu_buffer_rsrc_t rg = TileIO::rsrc(a.g + ge, kGroup * 4);
+        t.g0 = __builtin_amdgcn_raw_buffer_load_b128(rg, (int)(lane * 32), 0, SDL_AUX_LD);
+        t.g1 = __builtin_amdgcn_raw_buffer_load_b128(rg, (int)(lane * 32 + 16), 0, SDL_AUX_LD);
+#pragma unroll
+        for (int m = 0; m < MB; ++m)
+            t.w[m] = __builtin_amdgcn_raw_buffer_load_b128(TileIO::rsrc(a.w_send[m0 + m] + we, kGroup * 2),
+                                                           (int)(lane * 16), 0, SDL_AUX_LD);
+    } else {
+        // ragged tail or unaligned run: element by element under the buffer range check, which
+        // returns 0 past the end (g = 0 and w = 0 give an outer gradient of 0: no effect on a maximum)
+        const __amdgpu_buffer_rsrc_t rg = TileIO::rsrc(a.g + ge, valid * 4);
+        uint32_t x[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[j] = __builtin_amdgcn_raw_buffer_load_b32(rg, (int)((lane * 8 + j) * 4), 0, 0);
+        t.g0 = u32x4{x[0], x[1], x[2], x[3]};
+        t.g1 = u32x4{x[4], x[5], x[6], x[7]};
+#pragma unroll
+        for (int m = 0; m < MB; ++m) {
+            const __amdgpu_buffer_rsrc_t rw = TileIO::rsrc(a.w_send[m0 + m] + we, valid * 2);
+            uint32_t h[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                h[j] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rw, (int)((lane * 8 + j) * 2), 0, 0) & 0xffffu;
+            t.w[m] = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+        }
+    }
+}
+
+template <int MB>
+__global__ __launch_bounds__(kWave) void sdl_span_absmax_kernel(const Args a, const AbsmaxShare sh)
+{
+    const uint32_t lane = threadIdx.x;
+    uint32_t r = 0;
+    for (uint32_t i = 1; i < a.n_runs; ++i)
+        if (blockIdx.x >= sh.first[i]) r = i;
+    const Run run = a.runs[r];
+    const uint32_t k = blockIdx.x - sh.first[r], G = sh.G[r];
+    const uint64_t n_tiles = (run.numel + kGroup - 1) / kGroup;
+    const bool fast = run.vec != 0u;
+    auto valid_of = [&](uint64_t t) -> uint32_t {
+        const uint64_t rem = run.numel - t * kGroup;
+        return rem < (uint64_t)kGroup ? (uint32_t)rem : (uint32_t)kGroup;
+    };
+    auto g_elem = [&](uint64_t t) -> uint64_t { return (a.staged ? run.soff : run.offset) + t * kGroup; };
+
+    uint32_t amax[MB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m) amax[m] = 0u;
+
+    AbsmaxTile<MB> cur;
+    if (k < n_tiles) absmax_load<MB>(cur, a, sh.m0, g_elem(k), run.offset + (uint64_t)k * kGroup, valid_of(k), fast, lane);
+    for (uint64_t t = k; t < n_tiles; t += G) {
+        AbsmaxTile<MB> nxt = cur;
+        const uint64_t tn = t + G;
+        if (tn < n_tiles) absmax_load<MB>(nxt, a, sh.m0, g_elem(tn), run.offset + tn * kGroup, valid_of(tn), fast, lane);
+        const uint32_t gb[8] = {cur.g0.x, cur.g0.y, cur.g0.z, cur.g0.w, cur.g1.x, cur.g1.y, cur.g1.z, cur.g1.w};
+#pragma unroll
+        for (int m = 0; m < MB; ++m) {
+            const uint32_t wb[4] = {cur.w[m].x, cur.w[m].y, cur.w[m].z, cur.w[m].w};
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float d = u2f(gb[j]) - ((j & 1) ? bf16_hi(wb[j / 2]) : bf16_lo(wb[j / 2]));
+                const uint32_t mag = f2u(d) & 0x7fffffffu;
+                amax[m] = mag > amax[m] ? mag : amax[m];
+            }
+        }
+        cur = nxt;
+    }
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        const uint32_t v = lanes_max<kWave>(amax[m]);
+        if (lane == 0u && v != 0u)
+            __hip_atomic_fetch_max(reinterpret_cast<uint32_t*>(a.scales[sh.m0 + m]) + run.sidx, v, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 // Clears the scale words of a launch's runs before the whole-span maximum is accumulated.
 __global__ __launch_bounds__(SDL_MAX_WORKERS * kMaxRuns) void sdl_zero_span_scales(const Args a)
 {
@@ -839,6 +904,39 @@ hipError_t launch_f(const Args& a, uint32_t n_wg, hipStream_t s)
     }
 }
 
+// The whole-span maximum of every run of the launch: kAbsmaxGroups workgroups shared out among
+// the runs in proportion to their tiles (at least one each), replicas in blocks of 8 / 4 / 2 / 1.
+constexpr uint32_t kAbsmaxGroups = 8192;
+
+hipError_t launch_span_absmax(const Args& a, hipStream_t s)
+{
+    AbsmaxShare sh{};
+    uint64_t total_tiles = 0;
+    for (uint32_t r = 0; r < a.n_runs; ++r) total_tiles += (a.runs[r].numel + kGroup - 1) / kGroup;
+    uint32_t next = 0;
+    for (uint32_t r = 0; r < a.n_runs; ++r) {
+        const uint64_t tiles = (a.runs[r].numel + kGroup - 1) / kGroup;
+        uint64_t G = total_tiles ? (tiles * kAbsmaxGroups + total_tiles - 1) / total_tiles : 1;
+        if (G > tiles) G = tiles;
+        if (G < 1) G = 1;
+        sh.first[r] = next;
+        sh.G[r] = (uint32_t)G;
+        next += (uint32_t)G;
+    }
+    const dim3 grid(next), block(kWave);
+    for (uint32_t m0 = 0; m0 < a.M;) {
+        const uint32_t left = a.M - m0;
+        sh.m0 = m0;
+        if (left >= 8) { hipLaunchKernelGGL((sdl_span_absmax_kernel<8>), grid, block, 0, s, a, sh); m0 += 8; }
+        else if (left >= 4) { hipLaunchKernelGGL((sdl_span_absmax_kernel<4>), grid, block, 0, s, a, sh); m0 += 4; }
+        else if (left >= 2) { hipLaunchKernelGGL((sdl_span_absmax_kernel<2>), grid, block, 0, s, a, sh); m0 += 2; }
+        else { hipLaunchKernelGGL((sdl_span_absmax_kernel<1>), grid, block, 0, s, a, sh); m0 += 1; }
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 template <int MODE>
 hipError_t launch(const Args& a, sdl_format_t fmt, uint32_t n_wg, hipStream_t s)
 {
@@ -847,7 +945,7 @@ hipError_t launch(const Args& a, sdl_format_t fmt, uint32_t n_wg, hipStream_t s)
         if (is_span_scaled(fmt)) {
             // whole-span scale: clear the scale words, take the grid-wide maximum, then encode
             hipLaunchKernelGGL(sdl_zero_span_scales, dim3(1), dim3(SDL_MAX_WORKERS * kMaxRuns), 0, s, a);
-            hipError_t e = launch_m<kAbsmax, SDL_FMT_E3M0_SPAN, false, false>(a, n_wg, s);
+            hipError_t e = launch_span_absmax(a, s);
             if (e != hipSuccess) return e;
         }
     }
