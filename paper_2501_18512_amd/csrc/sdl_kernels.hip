@@ -905,7 +905,7 @@ hipError_t launch_f(const Args& a, uint32_t n_wg, hipStream_t s)
 }
 
 // The whole-span maximum of every run of the launch: kAbsmaxGroups workgroups shared out among
-// the runs in proportion to their tiles (at least one each), replicas in blocks of 8 / 4 / 2 / 1.
+// the runs in proportion to their tiles (at least one each), up to 8 replicas per launch.
 constexpr uint32_t kAbsmaxGroups = 8192;
 
 hipError_t launch_span_absmax(const Args& a, hipStream_t s)
@@ -927,10 +927,18 @@ hipError_t launch_span_absmax(const Args& a, hipStream_t s)
     for (uint32_t m0 = 0; m0 < a.M;) {
         const uint32_t left = a.M - m0;
         sh.m0 = m0;
-        if (left >= 8) { hipLaunchKernelGGL((sdl_span_absmax_kernel<8>), grid, block, 0, s, a, sh); m0 += 8; }
-        else if (left >= 4) { hipLaunchKernelGGL((sdl_span_absmax_kernel<4>), grid, block, 0, s, a, sh); m0 += 4; }
-        else if (left >= 2) { hipLaunchKernelGGL((sdl_span_absmax_kernel<2>), grid, block, 0, s, a, sh); m0 += 2; }
-        else { hipLaunchKernelGGL((sdl_span_absmax_kernel<1>), grid, block, 0, s, a, sh); m0 += 1; }
+        const uint32_t mb = left < 8u ? left : 8u;       // up to 8 replicas per pass over g
+        switch (mb) {
+        case 8: hipLaunchKernelGGL((sdl_span_absmax_kernel<8>), grid, block, 0, s, a, sh); break;
+        case 7: hipLaunchKernelGGL((sdl_span_absmax_kernel<7>), grid, block, 0, s, a, sh); break;
+        case 6: hipLaunchKernelGGL((sdl_span_absmax_kernel<6>), grid, block, 0, s, a, sh); break;
+        case 5: hipLaunchKernelGGL((sdl_span_absmax_kernel<5>), grid, block, 0, s, a, sh); break;
+        case 4: hipLaunchKernelGGL((sdl_span_absmax_kernel<4>), grid, block, 0, s, a, sh); break;
+        case 3: hipLaunchKernelGGL((sdl_span_absmax_kernel<3>), grid, block, 0, s, a, sh); break;
+        case 2: hipLaunchKernelGGL((sdl_span_absmax_kernel<2>), grid, block, 0, s, a, sh); break;
+        default: hipLaunchKernelGGL((sdl_span_absmax_kernel<1>), grid, block, 0, s, a, sh); break;
+        }
+        m0 += mb;
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
