@@ -249,7 +249,8 @@ def extras(st, fmt, wl, M, torch, sdl, args):
     res["dequant_reduce_nesterov"] = {"ms": t, "GB/s": (16 * n + M * (cb + sb)) / t / 1e6}
     t = time_gpu(torch, lambda: sdl.sdl_merge_overlap(g, wn, n, wl.alpha), steps, warm)
     res["merge_overlap"] = {"ms": t, "GB/s": (4 + 4 * M) * n / t / 1e6}
-    t = time_gpu(torch, lambda: sdl.sdl_fragment_outer_step(g, mom, ws, wn, n, fmt, wl.lr, wl.mu, wl.alpha),
+    work = scales if fmt == sdl.FMT_E3M0_SPAN else None          # the whole-span scale needs its scale words
+    t = time_gpu(torch, lambda: sdl.sdl_fragment_outer_step(g, mom, ws, wn, n, fmt, wl.lr, wl.mu, wl.alpha, None, work),
                  steps, warm)
     res["fused_single_run"] = {"ms": t, "GB/s": algorithmic_bytes_per_param(M, wl.tau) * n / t / 1e6}
     nbytes = (4 * n) // 16 * 16

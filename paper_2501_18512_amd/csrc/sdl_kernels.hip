@@ -29,6 +29,8 @@
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
+#include <new>
+#include <vector>
 
 #include "sdl.h"
 
@@ -135,11 +137,11 @@ __device__ __forceinline__ uint32_t lanes_max(uint32_t v)
         v = v > t ? v : t;
     }
     if constexpr (LANES >= 32) {
-        t = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((threadIdx.x ^ 16u) << 2), (int)v);   // lane ^ 16
+        t = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(((threadIdx.x ^ 16u) & 63u) << 2), (int)v);   // lane ^ 16
         v = v > t ? v : t;
     }
     if constexpr (LANES >= 64) {
-        t = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((threadIdx.x ^ 32u) << 2), (int)v);   // lane ^ 32
+        t = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(((threadIdx.x ^ 32u) & 63u) << 2), (int)v);   // lane ^ 32
         v = v > t ? v : t;
     }
     return v;
@@ -718,17 +720,37 @@ void sdl_kernel(const Args a)
 }
 
 // Pre-pass of the whole-span scale: the absolute maximum of every replica's outer gradient over
-// each run of the launch, folded into the run's scale word with an integer atomic maximum (the
-// words hold fp32 bit patterns of non-negative values, which order like the values).  A fixed
-// number of workgroups is shared out among the runs; workgroup k of a run walks the run's tiles
-// k, k + G, ... with 8 consecutive parameters per lane (128-bit loads, the next tile's loads issued
-// before the current tile is consumed), keeps the running maxima in registers, and touches the
-// scale words once at the very end -- one atomic per workgroup and replica instead of one per tile,
-// which all landed on the same few cache lines.
-struct AbsmaxShare {
-    uint32_t first[kMaxRuns];     // first workgroup of run r in this launch
-    uint32_t G[kMaxRuns];         // workgroups of run r (>= 1)
-    uint32_t m0;                  // first replica handled by this launch
+// each run, folded into the run's scale word with an integer atomic maximum (the words hold fp32
+// bit patterns of non-negative values, which order like the values).  It has an argument block of
+// its own, so that one launch covers up to 64 runs (a whole fragment as a rule).  A fixed number of
+// wavefronts is shared out among the runs; wavefront k of a run walks the run's tiles k, k + G, ...
+// with 8 consecutive parameters per lane (128-bit loads, the next tile's loads issued before the
+// current tile is consumed), keeps the running maxima in registers, and the scale words are touched
+// once at the very end -- one atomic per workgroup (4 wavefronts) and replica instead of one per
+// tile: atomics on one cache line are served one after the other, and the scale words of a launch
+// share a few lines.
+constexpr int kAbsmaxMaxRuns = 64;
+constexpr int kAbsmaxWaves = 4;       // wavefronts per workgroup (50 to 113 VGPRs)
+
+struct AbsmaxRun {
+    uint64_t offset;     // first element of the run in the flat arrays
+    uint64_t numel;
+    uint64_t soff;       // where the run starts in staged g (staged state only)
+    uint32_t vec;        // g and every w_send are 16-byte aligned at the run start
+    uint32_t sidx;       // index of the run's scale word
+    uint32_t first;      // first workgroup of the launch that works on this run
+    uint32_t G;          // workgroups of this run (>= 1)
+};
+
+struct AbsmaxArgs {
+    const float* g;
+    const uint16_t* w_send[SDL_MAX_WORKERS];
+    uint8_t* scales[SDL_MAX_WORKERS];
+    uint32_t M;
+    uint32_t m0;         // first replica handled by this launch
+    uint32_t staged;
+    uint32_t n_runs;
+    AbsmaxRun runs[kAbsmaxMaxRuns];
 };
 
 template <int MB>
@@ -738,7 +760,7 @@ struct AbsmaxTile {
 };
 
 template <int MB>
-__device__ __forceinline__ void absmax_load(AbsmaxTile<MB>& t, const Args& a, uint32_t m0, uint64_t ge, uint64_t we,
+__device__ __forceinline__ void absmax_load(AbsmaxTile<MB>& t, const AbsmaxArgs& a, uint64_t ge, uint64_t we,
                                             uint32_t valid, bool fast, uint32_t lane)
 {
     if (fast && valid == (uint32_t)kGroup) {
@@ -747,7 +769,7 @@ __device__ __forceinline__ void absmax_load(AbsmaxTile<MB>& t, const Args& a, ui
         t.g1 = __builtin_amdgcn_raw_buffer_load_b128(rg, (int)(lane * 32 + 16), 0, SDL_AUX_LD);
 #pragma unroll
         for (int m = 0; m < MB; ++m)
-            t.w[m] = __builtin_amdgcn_raw_buffer_load_b128(TileIO::rsrc(a.w_send[m0 + m] + we, kGroup * 2),
+            t.w[m] = __builtin_amdgcn_raw_buffer_load_b128(TileIO::rsrc(a.w_send[a.m0 + m] + we, kGroup * 2),
                                                            (int)(lane * 16), 0, SDL_AUX_LD);
     } else {
         // ragged tail or unaligned run: element by element under the buffer range check, which
@@ -760,7 +782,7 @@ __device__ __forceinline__ void absmax_load(AbsmaxTile<MB>& t, const Args& a, ui
         t.g1 = u32x4{x[4], x[5], x[6], x[7]};
 #pragma unroll
         for (int m = 0; m < MB; ++m) {
-            const __amdgpu_buffer_rsrc_t rw = TileIO::rsrc(a.w_send[m0 + m] + we, valid * 2);
+            const __amdgpu_buffer_rsrc_t rw = TileIO::rsrc(a.w_send[a.m0 + m] + we, valid * 2);
             uint32_t h[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j)
@@ -771,14 +793,21 @@ __device__ __forceinline__ void absmax_load(AbsmaxTile<MB>& t, const Args& a, ui
 }
 
 template <int MB>
-__global__ __launch_bounds__(kWave) void sdl_span_absmax_kernel(const Args a, const AbsmaxShare sh)
+__global__ __launch_bounds__(kWave * kAbsmaxWaves) void sdl_span_absmax_kernel(const AbsmaxArgs a)
 {
-    const uint32_t lane = threadIdx.x;
+    __shared__ uint32_t wave_max[kAbsmaxWaves][MB];
+    // the wavefront's number is the same in all of its lanes: say so, or every address derived from it
+    // is treated as different per lane and every buffer access is wrapped in a loop over lanes
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     uint32_t r = 0;
     for (uint32_t i = 1; i < a.n_runs; ++i)
-        if (blockIdx.x >= sh.first[i]) r = i;
-    const Run run = a.runs[r];
-    const uint32_t k = blockIdx.x - sh.first[r], G = sh.G[r];
+        if (blockIdx.x >= a.runs[i].first) r = i;
+    const AbsmaxRun run = a.runs[r];
+    // every wavefront of the run's workgroups walks its own tiles: k, k + G, ...; neighbouring
+    // tiles go to neighbouring workgroups (which the dispatcher deals to different XCDs), not to
+    // the wavefronts of one workgroup
+    const uint32_t k = wave * run.G + (blockIdx.x - run.first), G = run.G * kAbsmaxWaves;
     const uint64_t n_tiles = (run.numel + kGroup - 1) / kGroup;
     const bool fast = run.vec != 0u;
     auto valid_of = [&](uint64_t t) -> uint32_t {
@@ -792,11 +821,11 @@ __global__ __launch_bounds__(kWave) void sdl_span_absmax_kernel(const Args a, co
     for (int m = 0; m < MB; ++m) amax[m] = 0u;
 
     AbsmaxTile<MB> cur;
-    if (k < n_tiles) absmax_load<MB>(cur, a, sh.m0, g_elem(k), run.offset + (uint64_t)k * kGroup, valid_of(k), fast, lane);
+    if (k < n_tiles) absmax_load<MB>(cur, a, g_elem(k), run.offset + (uint64_t)k * kGroup, valid_of(k), fast, lane);
     for (uint64_t t = k; t < n_tiles; t += G) {
         AbsmaxTile<MB> nxt = cur;
         const uint64_t tn = t + G;
-        if (tn < n_tiles) absmax_load<MB>(nxt, a, sh.m0, g_elem(tn), run.offset + tn * kGroup, valid_of(tn), fast, lane);
+        if (tn < n_tiles) absmax_load<MB>(nxt, a, g_elem(tn), run.offset + tn * kGroup, valid_of(tn), fast, lane);
         const uint32_t gb[8] = {cur.g0.x, cur.g0.y, cur.g0.z, cur.g0.w, cur.g1.x, cur.g1.y, cur.g1.z, cur.g1.w};
 #pragma unroll
         for (int m = 0; m < MB; ++m) {
@@ -810,19 +839,30 @@ __global__ __launch_bounds__(kWave) void sdl_span_absmax_kernel(const Args a, co
         }
         cur = nxt;
     }
+    // wavefront, then workgroup (all of whose wavefronts work on the same run), then one atomic
+    // per workgroup and replica
 #pragma unroll
     for (int m = 0; m < MB; ++m) {
         const uint32_t v = lanes_max<kWave>(amax[m]);
-        if (lane == 0u && v != 0u)
-            __hip_atomic_fetch_max(reinterpret_cast<uint32_t*>(a.scales[sh.m0 + m]) + run.sidx, v, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+        if (lane == 0u) wave_max[wave][m] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < (uint32_t)MB) {
+        uint32_t v = 0u;
+        for (int w = 0; w < kAbsmaxWaves; ++w) v = wave_max[w][threadIdx.x] > v ? wave_max[w][threadIdx.x] : v;
+        // look before the atomic: reads of one cache line are served in parallel, atomics on it one
+        // after the other, and by the time most workgroups finish the word already holds a larger value
+        uint32_t* word = reinterpret_cast<uint32_t*>(a.scales[a.m0 + threadIdx.x]) + run.sidx;
+        if (v > __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+            __hip_atomic_fetch_max(word, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
-// Clears the scale words of a launch's runs before the whole-span maximum is accumulated.
-__global__ __launch_bounds__(SDL_MAX_WORKERS * kMaxRuns) void sdl_zero_span_scales(const Args a)
+// Clears the scale words of a pre-pass launch's runs before the maximum is accumulated
+// (thread = run * 16 + replica).
+__global__ __launch_bounds__(SDL_MAX_WORKERS * kAbsmaxMaxRuns) void sdl_zero_span_scales(const AbsmaxArgs a)
 {
-    const uint32_t m = threadIdx.x / kMaxRuns, r = threadIdx.x % kMaxRuns;
+    const uint32_t r = threadIdx.x / SDL_MAX_WORKERS, m = threadIdx.x % SDL_MAX_WORKERS;
     if (m < a.M && r < a.n_runs) reinterpret_cast<uint32_t*>(a.scales[m])[a.runs[r].sidx] = 0u;
 }
 
@@ -904,43 +944,56 @@ hipError_t launch_f(const Args& a, uint32_t n_wg, hipStream_t s)
     }
 }
 
-// The whole-span maximum of every run of the launch: kAbsmaxGroups workgroups shared out among
-// the runs in proportion to their tiles (at least one each), up to 8 replicas per launch.
+// Whole-span scale words of a list of runs: cleared, then the maximum of every replica's outer
+// gradient over each run.  kAbsmaxGroups wavefronts per launch are shared out among the runs in
+// proportion to their tiles (whole workgroups, at least one each); up to 8 replicas per pass over g.
 constexpr uint32_t kAbsmaxGroups = 8192;
 
-hipError_t launch_span_absmax(const Args& a, hipStream_t s)
+struct SpanRun { uint64_t offset, numel, soff; bool vec; uint32_t sidx; };
+
+hipError_t launch_span_prepass(const Args& a, const SpanRun* runs, uint32_t n_runs, hipStream_t s)
 {
-    AbsmaxShare sh{};
-    uint64_t total_tiles = 0;
-    for (uint32_t r = 0; r < a.n_runs; ++r) total_tiles += (a.runs[r].numel + kGroup - 1) / kGroup;
-    uint32_t next = 0;
-    for (uint32_t r = 0; r < a.n_runs; ++r) {
-        const uint64_t tiles = (a.runs[r].numel + kGroup - 1) / kGroup;
-        uint64_t G = total_tiles ? (tiles * kAbsmaxGroups + total_tiles - 1) / total_tiles : 1;
-        if (G > tiles) G = tiles;
-        if (G < 1) G = 1;
-        sh.first[r] = next;
-        sh.G[r] = (uint32_t)G;
-        next += (uint32_t)G;
-    }
-    const dim3 grid(next), block(kWave);
-    for (uint32_t m0 = 0; m0 < a.M;) {
-        const uint32_t left = a.M - m0;
-        sh.m0 = m0;
-        const uint32_t mb = left < 8u ? left : 8u;       // up to 8 replicas per pass over g
-        switch (mb) {
-        case 8: hipLaunchKernelGGL((sdl_span_absmax_kernel<8>), grid, block, 0, s, a, sh); break;
-        case 7: hipLaunchKernelGGL((sdl_span_absmax_kernel<7>), grid, block, 0, s, a, sh); break;
-        case 6: hipLaunchKernelGGL((sdl_span_absmax_kernel<6>), grid, block, 0, s, a, sh); break;
-        case 5: hipLaunchKernelGGL((sdl_span_absmax_kernel<5>), grid, block, 0, s, a, sh); break;
-        case 4: hipLaunchKernelGGL((sdl_span_absmax_kernel<4>), grid, block, 0, s, a, sh); break;
-        case 3: hipLaunchKernelGGL((sdl_span_absmax_kernel<3>), grid, block, 0, s, a, sh); break;
-        case 2: hipLaunchKernelGGL((sdl_span_absmax_kernel<2>), grid, block, 0, s, a, sh); break;
-        default: hipLaunchKernelGGL((sdl_span_absmax_kernel<1>), grid, block, 0, s, a, sh); break;
+    for (uint32_t r0 = 0; r0 < n_runs; r0 += kAbsmaxMaxRuns) {
+        AbsmaxArgs b{};
+        b.g = a.g;
+        b.M = a.M;
+        b.staged = a.staged;
+        for (uint32_t m = 0; m < a.M; ++m) { b.w_send[m] = a.w_send[m]; b.scales[m] = a.scales[m]; }
+        const uint32_t n = n_runs - r0 < (uint32_t)kAbsmaxMaxRuns ? n_runs - r0 : (uint32_t)kAbsmaxMaxRuns;
+        uint64_t total_tiles = 0;
+        for (uint32_t r = 0; r < n; ++r) total_tiles += (runs[r0 + r].numel + kGroup - 1) / kGroup;
+        uint32_t next = 0;
+        for (uint32_t r = 0; r < n; ++r) {
+            const SpanRun& in = runs[r0 + r];
+            const uint64_t tiles = (in.numel + kGroup - 1) / kGroup;
+            uint64_t waves = total_tiles ? (tiles * kAbsmaxGroups + total_tiles - 1) / total_tiles : 1;
+            if (waves > tiles) waves = tiles;
+            uint64_t G = (waves + kAbsmaxWaves - 1) / kAbsmaxWaves;
+            if (G < 1) G = 1;
+            b.runs[r] = AbsmaxRun{in.offset, in.numel, in.soff, in.vec ? 1u : 0u, in.sidx, next, (uint32_t)G};
+            next += (uint32_t)G;
         }
-        m0 += mb;
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
+        b.n_runs = n;
+        hipLaunchKernelGGL(sdl_zero_span_scales, dim3(1), dim3(SDL_MAX_WORKERS * kAbsmaxMaxRuns), 0, s, b);
+        const dim3 grid(next), block(kWave * kAbsmaxWaves);
+        for (uint32_t m0 = 0; m0 < a.M;) {
+            const uint32_t left = a.M - m0;
+            const uint32_t mb = left < 8u ? left : 8u;
+            b.m0 = m0;
+            switch (mb) {
+            case 8: hipLaunchKernelGGL((sdl_span_absmax_kernel<8>), grid, block, 0, s, b); break;
+            case 7: hipLaunchKernelGGL((sdl_span_absmax_kernel<7>), grid, block, 0, s, b); break;
+            case 6: hipLaunchKernelGGL((sdl_span_absmax_kernel<6>), grid, block, 0, s, b); break;
+            case 5: hipLaunchKernelGGL((sdl_span_absmax_kernel<5>), grid, block, 0, s, b); break;
+            case 4: hipLaunchKernelGGL((sdl_span_absmax_kernel<4>), grid, block, 0, s, b); break;
+            case 3: hipLaunchKernelGGL((sdl_span_absmax_kernel<3>), grid, block, 0, s, b); break;
+            case 2: hipLaunchKernelGGL((sdl_span_absmax_kernel<2>), grid, block, 0, s, b); break;
+            default: hipLaunchKernelGGL((sdl_span_absmax_kernel<1>), grid, block, 0, s, b); break;
+            }
+            m0 += mb;
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
     }
     return hipSuccess;
 }
@@ -949,14 +1002,6 @@ template <int MODE>
 hipError_t launch(const Args& a, sdl_format_t fmt, uint32_t n_wg, hipStream_t s)
 {
     if constexpr (MODE == kMerge) return launch_f<MODE, SDL_FMT_FP32>(a, n_wg, s);
-    if constexpr (MODE == kQuantize || MODE == kFused) {
-        if (is_span_scaled(fmt)) {
-            // whole-span scale: clear the scale words, take the grid-wide maximum, then encode
-            hipLaunchKernelGGL(sdl_zero_span_scales, dim3(1), dim3(SDL_MAX_WORKERS * kMaxRuns), 0, s, a);
-            hipError_t e = launch_span_absmax(a, s);
-            if (e != hipSuccess) return e;
-        }
-    }
     switch (fmt) {
     case SDL_FMT_FP32: return launch_f<MODE, SDL_FMT_FP32>(a, n_wg, s);
     case SDL_FMT_BF16: return launch_f<MODE, SDL_FMT_BF16>(a, n_wg, s);
@@ -994,6 +1039,13 @@ int run_single_span(Args& a, uint64_t n, sdl_format_t fmt, bool vec, void* strea
     if (n > (uint64_t)0x7fffffff * (uint64_t)kGroup) return SDL_ERR_UNSUPPORTED;
     RunBuilder rb(&a);
     rb.add(0, n, vec);
+    if constexpr (MODE == kQuantize || MODE == kFused) {
+        if (is_span_scaled(fmt)) {
+            // whole-span scale: clear the scale word, take the grid-wide maximum, then encode
+            const SpanRun one{0, n, 0, vec, 0};
+            if (launch_span_prepass(a, &one, 1, (hipStream_t)stream) != hipSuccess) return SDL_ERR_DEVICE;
+        }
+    }
     hipError_t e = launch<MODE>(a, fmt, (uint32_t)rb.n_wg, (hipStream_t)stream);
     return e == hipSuccess ? SDL_OK : SDL_ERR_DEVICE;
 }
@@ -1191,12 +1243,17 @@ static int launch_fragment(Args& a, const sdl_plan_t* plan, uint32_t p, bool vec
     if (is_span_scaled(fmt) && MODE != kMerge) rc = sdl_plan_fragment_spans(plan, p, &pieces, &n_pieces);
     else { pieces = runs; n_pieces = n_runs; }
     if (rc != SDL_OK) return rc;
-    // staged g / mom hold the fragment's runs back to back, each padded to whole tiles
-    uint64_t msg = 0, run_start = 0;
-    uint32_t run_i = 0;
-    for (uint32_t first = 0; first < n_pieces; first += kMaxRuns) {
-        RunBuilder rb(&a);
-        for (uint32_t i = first; i < n_pieces && i < first + kMaxRuns; ++i) {
+    // where every piece lies: in the flat arrays, in the message arrays (pieces back to back, each
+    // padded to whole tiles), and in staged g / mom (the fragment's runs back to back, each padded
+    // to whole tiles)
+    struct Piece { uint64_t offset, numel, msg, soff; bool vec; uint32_t sidx; };
+    std::vector<Piece> list;
+    std::vector<SpanRun> span_runs;
+    try {
+        list.reserve(n_pieces);
+        uint64_t msg = 0, run_start = 0;
+        uint32_t run_i = 0;
+        for (uint32_t i = 0; i < n_pieces; ++i) {
             if (pieces[i].numel == 0) continue;
             // the run that contains this piece, and where that run starts in the staged arrays
             while (run_i < n_runs && pieces[i].offset >= runs[run_i].offset + runs[run_i].numel) {
@@ -1206,11 +1263,26 @@ static int launch_fragment(Args& a, const sdl_plan_t* plan, uint32_t p, bool vec
             const uint64_t soff = run_i < n_runs ? run_start + (pieces[i].offset - runs[run_i].offset) : 0;
             // a piece keeps the 16-byte alignment of the bases when it starts on a multiple of 8 elements
             const bool piece_vec = vec && (pieces[i].offset % 8 == 0) && (!a.staged || soff % 8 == 0);
-            rb.add(pieces[i].offset, pieces[i].numel, piece_vec, msg, i, soff);
+            list.push_back(Piece{pieces[i].offset, pieces[i].numel, msg, soff, piece_vec, i});
             msg += (pieces[i].numel + kGroup - 1) / kGroup * kGroup;
         }
+        if (is_span_scaled(fmt) && (MODE == kQuantize || MODE == kFused)) {
+            span_runs.reserve(list.size());
+            for (const Piece& pc : list) span_runs.push_back(SpanRun{pc.offset, pc.numel, pc.soff, pc.vec, pc.sidx});
+        }
+    } catch (const std::bad_alloc&) {
+        return SDL_ERR_NOMEM;
+    }
+    if (!span_runs.empty()) {
+        // whole-span scale: clear the scale words, take the grid-wide maxima, then encode
+        if (launch_span_prepass(a, span_runs.data(), (uint32_t)span_runs.size(), (hipStream_t)stream) != hipSuccess)
+            return SDL_ERR_DEVICE;
+    }
+    for (size_t first = 0; first < list.size(); first += kMaxRuns) {
+        RunBuilder rb(&a);
+        for (size_t i = first; i < list.size() && i < first + kMaxRuns; ++i)
+            rb.add(list[i].offset, list[i].numel, list[i].vec, list[i].msg, list[i].sidx, list[i].soff);
         if (rb.n_wg > 0x7fffffffull) return SDL_ERR_UNSUPPORTED;
-        if (rb.n_wg == 0) continue;
         hipError_t e = launch<MODE>(a, fmt, (uint32_t)rb.n_wg, (hipStream_t)stream);
         if (e != hipSuccess) return SDL_ERR_DEVICE;
     }
