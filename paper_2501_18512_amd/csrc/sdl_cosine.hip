@@ -35,7 +35,7 @@ constexpr int kWave = 64;
 constexpr int kTile = kLaneElems * kWave;       // 512
 constexpr int kBlockM = 8;                      // replicas per side of one launch's block of the matrix
 constexpr int kMaxSets = 48;                    // parameter sets per launch
-constexpr int kWindows = 48;                    // windows a launch's sets are cut into (at least one per set)
+constexpr int kWindows = 48;                    // windows per launch: a set holding a share of 4/48 or more is cut
 constexpr int kMaxPieces = kMaxSets + kWindows;
 constexpr uint32_t kGroups = 8192;              // workgroups per launch, shared out among the sets (32 per compute unit)
 constexpr uint32_t kMaxGroups = 8192;           // what the workspace is sized for
