@@ -148,7 +148,7 @@ def test_config_stress_m8(fmt):
 
 def test_plan_call_with_many_ragged_runs():
     """More runs than one launch holds (16), ragged and partly unaligned: spans whose lengths are
-    not multiples of 32 are never joined, so every span is its own run, with its own block grid."""
+    not multiples of 128 end their run, so nearly every span is its own run, with its own block grid."""
     rng = np.random.default_rng(3)
     numel = [int(x) for x in rng.integers(1, 5000, 45)] + [4096, 512, 33, 2048 * 3]
     block = [i % 7 for i in range(len(numel))]
