@@ -31,9 +31,12 @@
  *     [32k, 32k+32) counted from the start of the span; the last may be partial.
  *   - fp32 arrays must be 4-byte aligned, bf16 arrays 2-byte aligned, code and
  *     scale arrays as the format needs (4 / 2 / 1 / 1 bytes for FP32 / BF16 /
- *     E4M3 / E3M0).  Arrays aligned to 16 bytes take the fast path; anything else
- *     is handled by a slower element-wise path with identical results.
- *     Misaligned pointers give SDL_ERR_ALIGNMENT.
+ *     E4M3 / E3M0); anything less gives SDL_ERR_ALIGNMENT.  Results do not depend
+ *     on alignment, speed does: full speed needs every array to start on a 128-byte
+ *     boundary (a cache line); model arrays (g, mom, replicas) that start elsewhere,
+ *     at any element, cost up to a fifth (lines shared between neighbouring tiles
+ *     are fetched twice); code arrays that are not 16-byte aligned put the whole
+ *     call on an element-by-element path at a quarter of the speed.
  *   - 1 <= M <= SDL_MAX_WORKERS.
  *   - No two arrays may overlap, except that w_send[m] may be the very same
  *     pointer as w_now[m] for every m (no overlap delay, tau = 0).
@@ -403,8 +406,8 @@ int sdl_engine_track_cosine(sdl_engine_t* engine, double* const* span_results, d
  * g (device, fp32) is only read for SDL_EVAL_OUTER and may be NULL otherwise; w (host array of
  * M device pointers, bf16) is only read for the other two and may be NULL for SDL_EVAL_OUTER.
  * out_bf16: device memory, numel bf16 values, owned by the caller; it must not overlap an input
- * it is not identical to.  Any numel and 2-/4-byte alignment; 16-byte aligned arrays take the fast
- * path.  Errors: SDL_ERR_INVALID_ARG (bad selector, M out of range, missing pointer),
+ * it is not identical to.  Any numel and 2-/4-byte alignment (full speed from 128-byte aligned
+ * arrays).  Errors: SDL_ERR_INVALID_ARG (bad selector, M out of range, missing pointer),
  * SDL_ERR_ALIGNMENT, SDL_ERR_UNSUPPORTED (numel above 2^40), SDL_ERR_DEVICE. */
 typedef enum { SDL_EVAL_FIRST_REPLICA = 0, SDL_EVAL_REPLICA_MEAN = 1, SDL_EVAL_OUTER = 2 } sdl_eval_params_t;
 int sdl_evaluation_params(sdl_eval_params_t which, const float* g, const void* const* w, uint32_t M, uint64_t numel,

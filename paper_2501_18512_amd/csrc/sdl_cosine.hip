@@ -89,8 +89,13 @@ struct TileRegs {
     u32x4 w[NW];
 };
 
+// 16 bytes at the alignment of an fp32 / a bf16 element
+typedef uint32_t u32x4_f32elem __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint32_t u32x4_bf16elem __attribute__((ext_vector_type(4), aligned(2)));
+
 // valid = parameters of the tile that exist (512 except in a set's last tile).  Full tiles of
-// aligned sets use 128-bit loads; anything else goes element by element under the buffer
+// aligned sets use 128-bit buffer loads, full tiles of sets that start at some other element
+// 128-bit loads of element alignment; a ragged last tile goes element by element under the buffer
 // range check, which returns 0 past the end (g = 0 and w = 0 give Delta = 0: no contribution).
 template <int NW>
 __device__ __forceinline__ void load_tile(TileRegs<NW>& t, const float* g, const uint16_t* (&w)[NW],
@@ -103,6 +108,13 @@ __device__ __forceinline__ void load_tile(TileRegs<NW>& t, const float* g, const
 #pragma unroll
         for (int m = 0; m < NW; ++m)
             t.w[m] = __builtin_amdgcn_raw_buffer_load_b128(rsrc(w[m] + e0, kTile * 2), (int)(lane * 16), 0, 2);
+    } else if (valid == (uint32_t)kTile) {
+        const u32x4_f32elem* pg = reinterpret_cast<const u32x4_f32elem*>(g + e0 + lane * kLaneElems);
+        t.g0 = __builtin_nontemporal_load(pg);
+        t.g1 = __builtin_nontemporal_load(pg + 1);
+#pragma unroll
+        for (int m = 0; m < NW; ++m)
+            t.w[m] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_bf16elem*>(w[m] + e0 + lane * kLaneElems));
     } else {
         const __amdgpu_buffer_rsrc_t rg = rsrc(g + e0, valid * 4);
         uint32_t x[kLaneElems];

@@ -44,11 +44,20 @@ __device__ __forceinline__ uint32_t bf16_pack(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
-// The lane's 8 bf16 of one array as 4 words (element 2k in the low half of word k).
+// 16 bytes at the alignment of an fp32 / a bf16 element
+typedef uint32_t u32x4_f32elem __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint32_t u32x4_bf16elem __attribute__((ext_vector_type(4), aligned(2)));
+
+// The lane's 8 bf16 of one array as 4 words (element 2k in the low half of word k): a 128-bit
+// buffer access in a whole tile when every array is 16-byte aligned, a 128-bit access of element
+// alignment in a whole tile otherwise, element by element under the buffer range check in a ragged
+// last tile.
 __device__ __forceinline__ u32x4 load_bf16x8(const uint16_t* p, uint64_t e0, uint32_t valid, bool fast, uint32_t lane)
 {
     if (fast && valid == (uint32_t)kTile)
         return __builtin_amdgcn_raw_buffer_load_b128(rsrc(p + e0, kTile * 2), (int)(lane * 16), 0, 2);
+    if (valid == (uint32_t)kTile)
+        return __builtin_nontemporal_load(reinterpret_cast<const u32x4_bf16elem*>(p + e0 + lane * kLaneElems));
     const __amdgpu_buffer_rsrc_t r = rsrc(p + e0, valid * 2);
     uint32_t h[kLaneElems];
 #pragma unroll
@@ -62,6 +71,11 @@ __device__ __forceinline__ void store_bf16x8(uint16_t* p, uint64_t e0, uint32_t 
 {
     if (fast && valid == (uint32_t)kTile) {
         __builtin_amdgcn_raw_buffer_store_b128(x, rsrc(p + e0, kTile * 2), (int)(lane * 16), 0, 2);
+        return;
+    }
+    if (valid == (uint32_t)kTile) {
+        __builtin_nontemporal_store(u32x4_bf16elem{x.x, x.y, x.z, x.w},
+                                    reinterpret_cast<u32x4_bf16elem*>(p + e0 + lane * kLaneElems));
         return;
     }
     const __amdgpu_buffer_rsrc_t r = rsrc(p + e0, valid * 2);      // stores past the end are dropped
@@ -89,6 +103,12 @@ __global__ void __launch_bounds__(kWave) sdl_eval_kernel(const EvalArgs a)
             const __amdgpu_buffer_rsrc_t r = rsrc(a.g + e0, kTile * 4);
             const u32x4 x0 = __builtin_amdgcn_raw_buffer_load_b128(r, (int)(lane * 32), 0, 2);
             const u32x4 x1 = __builtin_amdgcn_raw_buffer_load_b128(r, (int)(lane * 32 + 16), 0, 2);
+            v[0] = u2f(x0.x); v[1] = u2f(x0.y); v[2] = u2f(x0.z); v[3] = u2f(x0.w);
+            v[4] = u2f(x1.x); v[5] = u2f(x1.y); v[6] = u2f(x1.z); v[7] = u2f(x1.w);
+        } else if (valid == (uint32_t)kTile) {
+            const u32x4_f32elem* pg = reinterpret_cast<const u32x4_f32elem*>(a.g + e0 + lane * kLaneElems);
+            const u32x4_f32elem x0 = __builtin_nontemporal_load(pg);
+            const u32x4_f32elem x1 = __builtin_nontemporal_load(pg + 1);
             v[0] = u2f(x0.x); v[1] = u2f(x0.y); v[2] = u2f(x0.z); v[3] = u2f(x0.w);
             v[4] = u2f(x1.x); v[5] = u2f(x1.y); v[6] = u2f(x1.z); v[7] = u2f(x1.w);
         } else {

@@ -54,13 +54,20 @@ constexpr int block_elems(int f)
     return f == SDL_FMT_E3M0_B64 ? 64 : f == SDL_FMT_E3M0_B128 ? 128 : f == SDL_FMT_E3M0_SPAN ? 0 : SDL_BLOCK;
 }
 
+// How the whole tiles of a run reach memory (a ragged last tile always takes the guarded path).
+enum TilePath : uint32_t {
+    kPathGuarded = 0,   // element by element: some message array is not 16-byte aligned
+    kPathBuffer = 1,    // every array of the call is 16-byte aligned at the run's first element
+    kPathVector = 2,    // the message arrays are, the model arrays start at some other element
+};
+
 struct Run {
     uint64_t offset;     // first element of the run in the flat arrays
     uint64_t numel;
     uint64_t msg;        // where the run starts in the message arrays, in elements (a multiple of 512)
     uint64_t soff;       // where the run starts in staged g / mom arrays, in elements (staged state only)
     uint32_t first_wg;   // first workgroup of the launch that works on this run
-    uint32_t vec;        // 1: every array of this run is 16-byte aligned at its start
+    uint32_t path;       // TilePath of the run's whole tiles
     uint32_t sidx;       // whole-span scale: index of the run's 4-byte scale word
     uint32_t pad_;
 };
@@ -299,10 +306,18 @@ __device__ __forceinline__ void decode_e4m3(uint32_t c0, float scale, float (&dq
 // of row `row` of each array.
 //   TileIO     a whole, 16-byte aligned tile: buffer loads / stores through one resource
 //              per array (scalar base, 32-bit lane offset) with explicit cache policy
+//   TileIOT<false>  a whole tile whose model arrays start at any element (a run behind a
+//              parameter group of odd length): the same lane layout through plain vector
+//              loads / stores of element alignment; the message arrays as in TileIO
 //   GuardedIO  any alignment, any tail: per-element global loads / stores under a
 //              per-row count of valid elements
 
-struct TileIO {
+// vectors of element alignment: the compiler picks the widest access the target allows
+typedef float f32x4_elem __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint32_t u32x2_elem __attribute__((ext_vector_type(2), aligned(2)));
+
+template <bool ALIGNED>
+struct TileIOT {
     const Args& a;
     uint64_t t0;      // tile's first element in the flat arrays (workgroup uniform)
     uint64_t tb;      // tile's first element in the message arrays (a multiple of 512)
@@ -365,13 +380,53 @@ struct TileIO {
                                               SDL_AUX_ST);
     }
 
-    __device__ __forceinline__ void load_g(int row, float (&v)[kVec]) const { ld_f32(a.g + s0, row, v); }
-    __device__ __forceinline__ void load_mom(int row, float (&v)[kVec]) const { ld_f32(a.mom + s0, row, v); }
-    __device__ __forceinline__ void store_g(int row, const float (&v)[kVec]) const { st_f32(a.g + s0, row, v); }
-    __device__ __forceinline__ void store_mom(int row, const float (&v)[kVec]) const { st_f32(a.mom + s0, row, v); }
-    __device__ __forceinline__ void load_ws(uint32_t m, int row, uint32_t (&u)[2]) const { ld_bf16(a.w_send[m] + t0, row, u); }
-    __device__ __forceinline__ void load_wn(uint32_t m, int row, uint32_t (&u)[2]) const { ld_bf16(a.w_now[m] + t0, row, u); }
-    __device__ __forceinline__ void store_wn(uint32_t m, int row, const uint32_t (&u)[2]) const { st_bf16(a.w_now[m] + t0, row, u); }
+    // the model arrays: the buffer path above when the tile is 16-byte aligned in all of them,
+    // element-aligned vectors (non-temporal as well) otherwise
+    __device__ __forceinline__ void model_ld_f32(const float* p, int row, float (&v)[kVec]) const
+    {
+        if constexpr (ALIGNED) {
+            ld_f32(p, row, v);
+        } else {
+            const f32x4_elem x =
+                __builtin_nontemporal_load(reinterpret_cast<const f32x4_elem*>(p + row * kRow + lane * kVec));
+            v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+        }
+    }
+    __device__ __forceinline__ void model_st_f32(float* p, int row, const float (&v)[kVec]) const
+    {
+        if constexpr (ALIGNED) {
+            st_f32(p, row, v);
+        } else {
+            const f32x4_elem x = {v[0], v[1], v[2], v[3]};
+            __builtin_nontemporal_store(x, reinterpret_cast<f32x4_elem*>(p + row * kRow + lane * kVec));
+        }
+    }
+    __device__ __forceinline__ void model_ld_bf16(const uint16_t* p, int row, uint32_t (&u)[2]) const
+    {
+        if constexpr (ALIGNED) {
+            ld_bf16(p, row, u);
+        } else {
+            const u32x2_elem x =
+                __builtin_nontemporal_load(reinterpret_cast<const u32x2_elem*>(p + row * kRow + lane * kVec));
+            u[0] = x.x; u[1] = x.y;
+        }
+    }
+    __device__ __forceinline__ void model_st_bf16(uint16_t* p, int row, const uint32_t (&u)[2]) const
+    {
+        if constexpr (ALIGNED) {
+            st_bf16(p, row, u);
+        } else {
+            const u32x2_elem x = {u[0], u[1]};
+            __builtin_nontemporal_store(x, reinterpret_cast<u32x2_elem*>(p + row * kRow + lane * kVec));
+        }
+    }
+    __device__ __forceinline__ void load_g(int row, float (&v)[kVec]) const { model_ld_f32(a.g + s0, row, v); }
+    __device__ __forceinline__ void load_mom(int row, float (&v)[kVec]) const { model_ld_f32(a.mom + s0, row, v); }
+    __device__ __forceinline__ void store_g(int row, const float (&v)[kVec]) const { model_st_f32(a.g + s0, row, v); }
+    __device__ __forceinline__ void store_mom(int row, const float (&v)[kVec]) const { model_st_f32(a.mom + s0, row, v); }
+    __device__ __forceinline__ void load_ws(uint32_t m, int row, uint32_t (&u)[2]) const { model_ld_bf16(a.w_send[m] + t0, row, u); }
+    __device__ __forceinline__ void load_wn(uint32_t m, int row, uint32_t (&u)[2]) const { model_ld_bf16(a.w_now[m] + t0, row, u); }
+    __device__ __forceinline__ void store_wn(uint32_t m, int row, const uint32_t (&u)[2]) const { model_st_bf16(a.w_now[m] + t0, row, u); }
 
     // E4M3 only: with EXACT = false the two byte values the encoder never writes decode to NaN
     static constexpr bool kHasInexactDecode = true;
@@ -423,6 +478,8 @@ struct TileIO {
         }
     }
 };
+
+using TileIO = TileIOT<true>;
 
 struct GuardedIO {
     const Args& a;
@@ -708,9 +765,14 @@ void sdl_kernel(const Args a)
     const uint64_t run_off = a.runs[r].offset;
     const uint64_t run_n = a.runs[r].numel;
     const uint64_t tile = (uint64_t)(wg - a.runs[r].first_wg) * kGroup;   // first element of the tile in the run
-    if (a.runs[r].vec && run_n - tile >= (uint64_t)kGroup) {
+    const bool whole = run_n - tile >= (uint64_t)kGroup;
+    if (whole && a.runs[r].path == kPathBuffer) {
         const TileIO io{a, run_off + tile, a.runs[r].msg + tile, threadIdx.x, a.runs[r].sidx,
                         a.staged ? a.runs[r].soff + tile : run_off + tile};
+        process<MODE, FMT, MT, ALIASED, EMIT>(a, io);
+    } else if (whole && a.runs[r].path == kPathVector) {
+        const TileIOT<false> io{a, run_off + tile, a.runs[r].msg + tile, threadIdx.x, a.runs[r].sidx,
+                                a.staged ? a.runs[r].soff + tile : run_off + tile};
         process<MODE, FMT, MT, ALIASED, EMIT>(a, io);
     } else {
         const GuardedIO io{a, run_off + tile, tile, a.runs[r].msg + tile, run_n, threadIdx.x, a.runs[r].sidx,
@@ -753,6 +815,10 @@ struct AbsmaxArgs {
     AbsmaxRun runs[kAbsmaxMaxRuns];
 };
 
+// 16 bytes at the alignment of an fp32 / a bf16 element
+typedef uint32_t u32x4_f32elem __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint32_t u32x4_bf16elem __attribute__((ext_vector_type(4), aligned(2)));
+
 template <int MB>
 struct AbsmaxTile {
     u32x4 g0, g1;
@@ -771,9 +837,18 @@ __device__ __forceinline__ void absmax_load(AbsmaxTile<MB>& t, const AbsmaxArgs&
         for (int m = 0; m < MB; ++m)
             t.w[m] = __builtin_amdgcn_raw_buffer_load_b128(TileIO::rsrc(a.w_send[a.m0 + m] + we, kGroup * 2),
                                                            (int)(lane * 16), 0, SDL_AUX_LD);
+    } else if (valid == (uint32_t)kGroup) {
+        // a whole tile of a run that starts at some other element: vectors of element alignment
+        const u32x4_f32elem* pg = reinterpret_cast<const u32x4_f32elem*>(a.g + ge + lane * 8);
+        t.g0 = __builtin_nontemporal_load(pg);
+        t.g1 = __builtin_nontemporal_load(pg + 1);
+#pragma unroll
+        for (int m = 0; m < MB; ++m)
+            t.w[m] = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4_bf16elem*>(a.w_send[a.m0 + m] + we + lane * 8));
     } else {
-        // ragged tail or unaligned run: element by element under the buffer range check, which
-        // returns 0 past the end (g = 0 and w = 0 give an outer gradient of 0: no effect on a maximum)
+        // ragged tail: element by element under the buffer range check, which returns 0 past the
+        // end (g = 0 and w = 0 give an outer gradient of 0: no effect on a maximum)
         const __amdgpu_buffer_rsrc_t rg = TileIO::rsrc(a.g + ge, valid * 4);
         uint32_t x[8];
 #pragma unroll
@@ -1015,34 +1090,41 @@ hipError_t launch(const Args& a, sdl_format_t fmt, uint32_t n_wg, hipStream_t s)
 
 bool valid_format(sdl_format_t fmt) { return fmt >= SDL_FMT_FP32 && fmt <= SDL_FMT_E3M0_SPAN; }
 
-// Fill a.runs from a list of (offset, numel); returns the number of workgroups.  vec is
-// set per run when every array used by the call is 16-byte aligned at the run start.
+// 16-byte alignment of a call's pointers: model = g, mom and the replicas; msg = codes (scale
+// bytes need none).
+struct Align16 {
+    bool model = true, msg = true;
+    TilePath path() const { return !msg ? kPathGuarded : model ? kPathBuffer : kPathVector; }
+    Align16 at(bool run_start_aligned) const { return Align16{model && run_start_aligned, msg}; }
+};
+
+// Fill a.runs from a list of (offset, numel); returns the number of workgroups.
 struct RunBuilder {
     Args* a;
     uint64_t n_wg = 0;
     explicit RunBuilder(Args* args) : a(args) { a->n_runs = 0; }
     bool full() const { return a->n_runs == kMaxRuns; }
-    void add(uint64_t offset, uint64_t numel, bool vec, uint64_t msg = 0, uint32_t sidx = 0, uint64_t soff = 0)
+    void add(uint64_t offset, uint64_t numel, TilePath path, uint64_t msg = 0, uint32_t sidx = 0, uint64_t soff = 0)
     {
         Run& r = a->runs[a->n_runs++];
         r.offset = offset; r.numel = numel; r.msg = msg; r.soff = soff; r.first_wg = (uint32_t)n_wg;
-        r.vec = vec ? 1u : 0u; r.sidx = sidx; r.pad_ = 0;
+        r.path = path; r.sidx = sidx; r.pad_ = 0;
         n_wg += (numel + kGroup - 1) / kGroup;
     }
 };
 
 // One span starting at the given pointers (offset 0).
 template <int MODE>
-int run_single_span(Args& a, uint64_t n, sdl_format_t fmt, bool vec, void* stream)
+int run_single_span(Args& a, uint64_t n, sdl_format_t fmt, Align16 al, void* stream)
 {
     if (n == 0) return SDL_OK;
     if (n > (uint64_t)0x7fffffff * (uint64_t)kGroup) return SDL_ERR_UNSUPPORTED;
     RunBuilder rb(&a);
-    rb.add(0, n, vec);
+    rb.add(0, n, al.path());
     if constexpr (MODE == kQuantize || MODE == kFused) {
         if (is_span_scaled(fmt)) {
             // whole-span scale: clear the scale word, take the grid-wide maximum, then encode
-            const SpanRun one{0, n, 0, vec, 0};
+            const SpanRun one{0, n, 0, al.model, 0};
             if (launch_span_prepass(a, &one, 1, (hipStream_t)stream) != hipSuccess) return SDL_ERR_DEVICE;
         }
     }
@@ -1065,18 +1147,20 @@ int sdl_quantize_outer_grad(const float* g, const void* const* w_send, uint32_t 
     std::memset(&a, 0, sizeof(a));
     a.g = const_cast<float*>(g);
     a.M = M;
-    bool vec = aligned(g, 16);
+    Align16 al;
+    al.model = aligned(g, 16);
     if (!aligned(g, 4)) return SDL_ERR_ALIGNMENT;
     for (uint32_t m = 0; m < M; ++m) {
         if (!w_send[m] || !codes[m] || (scaled && !scales[m])) return SDL_ERR_INVALID_ARG;
         if (!aligned(w_send[m], 2) || !aligned(codes[m], code_align(fmt))) return SDL_ERR_ALIGNMENT;
         if (scaled && !aligned(scales[m], scale_align(fmt))) return SDL_ERR_ALIGNMENT;
-        vec = vec && aligned(w_send[m], 16) && aligned(codes[m], 16);
+        al.model = al.model && aligned(w_send[m], 16);
+        al.msg = al.msg && aligned(codes[m], 16);
         a.w_send[m] = static_cast<const uint16_t*>(w_send[m]);
         a.codes[m] = static_cast<uint8_t*>(codes[m]);
         a.scales[m] = scaled ? static_cast<uint8_t*>(scales[m]) : nullptr;
     }
-    return run_single_span<kQuantize>(a, n, fmt, vec, stream);
+    return run_single_span<kQuantize>(a, n, fmt, al, stream);
 }
 
 int sdl_dequant_reduce_nesterov(float* g, float* mom, const void* const* codes,
@@ -1091,22 +1175,23 @@ int sdl_dequant_reduce_nesterov(float* g, float* mom, const void* const* codes,
     Args a;
     std::memset(&a, 0, sizeof(a));
     a.g = g; a.mom = mom; a.M = M; a.lr = lr; a.mu = mu;
-    bool vec = aligned(g, 16) && aligned(mom, 16);
+    Align16 al;
+    al.model = aligned(g, 16) && aligned(mom, 16);
     for (uint32_t m = 0; m < M; ++m) {
         if (!codes[m] || (scaled && !scales[m])) return SDL_ERR_INVALID_ARG;
         if (!aligned(codes[m], code_align(fmt))) return SDL_ERR_ALIGNMENT;
         if (scaled && !aligned(scales[m], scale_align(fmt))) return SDL_ERR_ALIGNMENT;
-        vec = vec && aligned(codes[m], 16);
+        al.msg = al.msg && aligned(codes[m], 16);
         a.codes[m] = static_cast<uint8_t*>(const_cast<void*>(codes[m]));
         a.scales[m] = scaled ? static_cast<uint8_t*>(const_cast<void*>(scales[m])) : nullptr;
     }
-    return run_single_span<kReduce>(a, n, fmt, vec, stream);
+    return run_single_span<kReduce>(a, n, fmt, al, stream);
 }
 
 // Argument marshalling shared by the receive-side calls that also merge.
 static int fill_receive_args(Args& a, float* g, float* mom, const void* const* codes, const void* const* scales,
                              void* const* w_now, uint32_t M, sdl_format_t fmt, float lr, float mu, float alpha,
-                             bool* vec)
+                             Align16* al)
 {
     if (!valid_format(fmt) || M == 0 || M > SDL_MAX_WORKERS) return SDL_ERR_INVALID_ARG;
     const bool scaled = is_scaled(fmt);
@@ -1114,12 +1199,13 @@ static int fill_receive_args(Args& a, float* g, float* mom, const void* const* c
     if (!aligned(g, 4) || !aligned(mom, 4)) return SDL_ERR_ALIGNMENT;
     std::memset(&a, 0, sizeof(a));
     a.g = g; a.mom = mom; a.M = M; a.lr = lr; a.mu = mu; a.alpha = alpha; a.one_minus_alpha = 1.0f - alpha;
-    *vec = aligned(g, 16) && aligned(mom, 16);
+    *al = Align16{aligned(g, 16) && aligned(mom, 16), true};
     for (uint32_t m = 0; m < M; ++m) {
         if (!codes[m] || !w_now[m] || (scaled && !scales[m])) return SDL_ERR_INVALID_ARG;
         if (!aligned(codes[m], code_align(fmt)) || !aligned(w_now[m], 2)) return SDL_ERR_ALIGNMENT;
         if (scaled && !aligned(scales[m], scale_align(fmt))) return SDL_ERR_ALIGNMENT;
-        *vec = *vec && aligned(codes[m], 16) && aligned(w_now[m], 16);
+        al->model = al->model && aligned(w_now[m], 16);
+        al->msg = al->msg && aligned(codes[m], 16);
         a.codes[m] = static_cast<uint8_t*>(const_cast<void*>(codes[m]));
         a.scales[m] = scaled ? static_cast<uint8_t*>(const_cast<void*>(scales[m])) : nullptr;
         a.w_now[m] = static_cast<uint16_t*>(w_now[m]);
@@ -1133,10 +1219,10 @@ int sdl_receive_outer_step(float* g, float* mom, const void* const* codes, const
 {
     if (n == 0) return (valid_format(fmt) && M >= 1 && M <= SDL_MAX_WORKERS) ? SDL_OK : SDL_ERR_INVALID_ARG;
     Args a;
-    bool vec = false;
-    int rc = fill_receive_args(a, g, mom, codes, scales, w_now, M, fmt, lr, mu, alpha, &vec);
+    Align16 al;
+    int rc = fill_receive_args(a, g, mom, codes, scales, w_now, M, fmt, lr, mu, alpha, &al);
     if (rc != SDL_OK) return rc;
-    return run_single_span<kReceive>(a, n, fmt, vec, stream);
+    return run_single_span<kReceive>(a, n, fmt, al, stream);
 }
 
 int sdl_merge_overlap(const float* g_new, void* const* w_now, uint32_t M, uint64_t n, float alpha,
@@ -1149,19 +1235,20 @@ int sdl_merge_overlap(const float* g_new, void* const* w_now, uint32_t M, uint64
     Args a;
     std::memset(&a, 0, sizeof(a));
     a.g = const_cast<float*>(g_new); a.M = M; a.alpha = alpha; a.one_minus_alpha = 1.0f - alpha;
-    bool vec = aligned(g_new, 16);
+    Align16 al;
+    al.model = aligned(g_new, 16);
     for (uint32_t m = 0; m < M; ++m) {
         if (!w_now[m]) return SDL_ERR_INVALID_ARG;
         if (!aligned(w_now[m], 2)) return SDL_ERR_ALIGNMENT;
-        vec = vec && aligned(w_now[m], 16);
+        al.model = al.model && aligned(w_now[m], 16);
         a.w_now[m] = static_cast<uint16_t*>(w_now[m]);
     }
-    return run_single_span<kMerge>(a, n, SDL_FMT_FP32, vec, stream);
+    return run_single_span<kMerge>(a, n, SDL_FMT_FP32, al, stream);
 }
 
 // Shared argument marshalling of the two fused entry points.
 static int fill_fused_args(Args& a, float* g, float* mom, const void* const* w_send, void* const* w_now,
-                           uint32_t M, sdl_format_t fmt, float lr, float mu, float alpha, bool* vec)
+                           uint32_t M, sdl_format_t fmt, float lr, float mu, float alpha, Align16* al)
 {
     if (!valid_format(fmt) || M == 0 || M > SDL_MAX_WORKERS) return SDL_ERR_INVALID_ARG;
     if (!g || !mom || !w_send || !w_now) return SDL_ERR_INVALID_ARG;
@@ -1169,12 +1256,12 @@ static int fill_fused_args(Args& a, float* g, float* mom, const void* const* w_s
     std::memset(&a, 0, sizeof(a));
     a.g = g; a.mom = mom; a.M = M; a.lr = lr; a.mu = mu; a.alpha = alpha;
     a.one_minus_alpha = 1.0f - alpha;
-    *vec = aligned(g, 16) && aligned(mom, 16);
+    *al = Align16{aligned(g, 16) && aligned(mom, 16), true};
     uint32_t same = 0;
     for (uint32_t m = 0; m < M; ++m) {
         if (!w_send[m] || !w_now[m]) return SDL_ERR_INVALID_ARG;
         if (!aligned(w_send[m], 2) || !aligned(w_now[m], 2)) return SDL_ERR_ALIGNMENT;
-        *vec = *vec && aligned(w_send[m], 16) && aligned(w_now[m], 16);
+        al->model = al->model && aligned(w_send[m], 16) && aligned(w_now[m], 16);
         same += (w_send[m] == w_now[m]);
         a.w_send[m] = static_cast<const uint16_t*>(w_send[m]);
         a.w_now[m] = static_cast<uint16_t*>(w_now[m]);
@@ -1187,7 +1274,7 @@ static int fill_fused_args(Args& a, float* g, float* mom, const void* const* w_s
 // Optional message outputs of a fused call; the whole-span scale needs its scale words as
 // workspace even when no message is written.
 static int attach_fused_messages(Args& a, uint32_t M, sdl_format_t fmt, void* const* codes_or_null,
-                                 void* const* scales_or_null, bool* vec)
+                                 void* const* scales_or_null, Align16* al)
 {
     if (codes_or_null) {
         const bool scaled = is_scaled(fmt);
@@ -1195,7 +1282,7 @@ static int attach_fused_messages(Args& a, uint32_t M, sdl_format_t fmt, void* co
         for (uint32_t m = 0; m < M; ++m) {
             if (!codes_or_null[m] || (scaled && !scales_or_null[m])) return SDL_ERR_INVALID_ARG;
             if (!aligned(codes_or_null[m], code_align(fmt))) return SDL_ERR_ALIGNMENT;
-            *vec = *vec && aligned(codes_or_null[m], 16);
+            al->msg = al->msg && aligned(codes_or_null[m], 16);
             a.codes[m] = static_cast<uint8_t*>(codes_or_null[m]);
             a.scales[m] = scaled ? static_cast<uint8_t*>(scales_or_null[m]) : nullptr;
         }
@@ -1218,12 +1305,12 @@ int sdl_fragment_outer_step(float* g, float* mom, const void* const* w_send, voi
 {
     if (n == 0) return (valid_format(fmt) && M >= 1 && M <= SDL_MAX_WORKERS) ? SDL_OK : SDL_ERR_INVALID_ARG;
     Args a;
-    bool vec = false;
-    int rc = fill_fused_args(a, g, mom, w_send, w_now, M, fmt, lr, mu, alpha, &vec);
+    Align16 al;
+    int rc = fill_fused_args(a, g, mom, w_send, w_now, M, fmt, lr, mu, alpha, &al);
     if (rc != SDL_OK) return rc;
-    rc = attach_fused_messages(a, M, fmt, codes_or_null, scales_or_null, &vec);
+    rc = attach_fused_messages(a, M, fmt, codes_or_null, scales_or_null, &al);
     if (rc != SDL_OK) return rc;
-    return run_single_span<kFused>(a, n, fmt, vec, stream);
+    return run_single_span<kFused>(a, n, fmt, al, stream);
 }
 
 }  // extern "C"
@@ -1231,7 +1318,7 @@ int sdl_fragment_outer_step(float* g, float* mom, const void* const* w_send, voi
 // One mode over all runs of fragment p, on flat model arrays; the fragment's messages are
 // the concatenation of its runs, each padded to a whole number of 512-element tiles.
 template <int MODE>
-static int launch_fragment(Args& a, const sdl_plan_t* plan, uint32_t p, bool vec, sdl_format_t fmt, void* stream)
+static int launch_fragment(Args& a, const sdl_plan_t* plan, uint32_t p, Align16 al, sdl_format_t fmt, void* stream)
 {
     // the pieces that are processed: joined runs, or, for the whole-span scale, the spans
     // themselves (one scale word per parameter group)
@@ -1246,7 +1333,7 @@ static int launch_fragment(Args& a, const sdl_plan_t* plan, uint32_t p, bool vec
     // where every piece lies: in the flat arrays, in the message arrays (pieces back to back, each
     // padded to whole tiles), and in staged g / mom (the fragment's runs back to back, each padded
     // to whole tiles)
-    struct Piece { uint64_t offset, numel, msg, soff; bool vec; uint32_t sidx; };
+    struct Piece { uint64_t offset, numel, msg, soff; Align16 al; uint32_t sidx; };
     std::vector<Piece> list;
     std::vector<SpanRun> span_runs;
     try {
@@ -1262,13 +1349,13 @@ static int launch_fragment(Args& a, const sdl_plan_t* plan, uint32_t p, bool vec
             }
             const uint64_t soff = run_i < n_runs ? run_start + (pieces[i].offset - runs[run_i].offset) : 0;
             // a piece keeps the 16-byte alignment of the bases when it starts on a multiple of 8 elements
-            const bool piece_vec = vec && (pieces[i].offset % 8 == 0) && (!a.staged || soff % 8 == 0);
-            list.push_back(Piece{pieces[i].offset, pieces[i].numel, msg, soff, piece_vec, i});
+            const Align16 piece_al = al.at((pieces[i].offset % 8 == 0) && (!a.staged || soff % 8 == 0));
+            list.push_back(Piece{pieces[i].offset, pieces[i].numel, msg, soff, piece_al, i});
             msg += (pieces[i].numel + kGroup - 1) / kGroup * kGroup;
         }
         if (is_span_scaled(fmt) && (MODE == kQuantize || MODE == kFused)) {
             span_runs.reserve(list.size());
-            for (const Piece& pc : list) span_runs.push_back(SpanRun{pc.offset, pc.numel, pc.soff, pc.vec, pc.sidx});
+            for (const Piece& pc : list) span_runs.push_back(SpanRun{pc.offset, pc.numel, pc.soff, pc.al.model, pc.sidx});
         }
     } catch (const std::bad_alloc&) {
         return SDL_ERR_NOMEM;
@@ -1281,7 +1368,7 @@ static int launch_fragment(Args& a, const sdl_plan_t* plan, uint32_t p, bool vec
     for (size_t first = 0; first < list.size(); first += kMaxRuns) {
         RunBuilder rb(&a);
         for (size_t i = first; i < list.size() && i < first + kMaxRuns; ++i)
-            rb.add(list[i].offset, list[i].numel, list[i].vec, list[i].msg, list[i].sidx, list[i].soff);
+            rb.add(list[i].offset, list[i].numel, list[i].al.path(), list[i].msg, list[i].sidx, list[i].soff);
         if (rb.n_wg > 0x7fffffffull) return SDL_ERR_UNSUPPORTED;
         hipError_t e = launch<MODE>(a, fmt, (uint32_t)rb.n_wg, (hipStream_t)stream);
         if (e != hipSuccess) return SDL_ERR_DEVICE;
@@ -1316,13 +1403,13 @@ static int fused_fragment(const sdl_plan_t* plan, uint32_t p, float* g_base, flo
     // the whole-span scale needs scale words as workspace: only the calls that take them support it
     if (valid_format(fmt) && is_span_scaled(fmt) && !scales_or_null) return SDL_ERR_UNSUPPORTED;
     Args a;
-    bool vec = false;
-    int rc = fill_fused_args(a, g_base, mom_base, w_send_base, w_now_base, M, fmt, lr, mu, alpha, &vec);
+    Align16 al;
+    int rc = fill_fused_args(a, g_base, mom_base, w_send_base, w_now_base, M, fmt, lr, mu, alpha, &al);
     if (rc != SDL_OK) return rc;
-    rc = attach_fused_messages(a, M, fmt, codes_or_null, scales_or_null, &vec);
+    rc = attach_fused_messages(a, M, fmt, codes_or_null, scales_or_null, &al);
     if (rc != SDL_OK) return rc;
     a.staged = staged ? 1u : 0u;
-    return launch_fragment<kFused>(a, plan, p, vec, fmt, stream);
+    return launch_fragment<kFused>(a, plan, p, al, fmt, stream);
 }
 
 static int quantize_fragment(const sdl_plan_t* plan, uint32_t p, const float* g_base,
@@ -1338,18 +1425,20 @@ static int quantize_fragment(const sdl_plan_t* plan, uint32_t p, const float* g_
     std::memset(&a, 0, sizeof(a));
     a.g = const_cast<float*>(g_base);
     a.M = M;
-    bool vec = aligned(g_base, 16);
+    Align16 al;
+    al.model = aligned(g_base, 16);
     for (uint32_t m = 0; m < M; ++m) {
         if (!w_send_base[m] || !codes[m] || (scaled && !scales[m])) return SDL_ERR_INVALID_ARG;
         if (!aligned(w_send_base[m], 2) || !aligned(codes[m], code_align(fmt))) return SDL_ERR_ALIGNMENT;
         if (scaled && !aligned(scales[m], scale_align(fmt))) return SDL_ERR_ALIGNMENT;
-        vec = vec && aligned(w_send_base[m], 16) && aligned(codes[m], 16);
+        al.model = al.model && aligned(w_send_base[m], 16);
+        al.msg = al.msg && aligned(codes[m], 16);
         a.w_send[m] = static_cast<const uint16_t*>(w_send_base[m]);
         a.codes[m] = static_cast<uint8_t*>(codes[m]);
         a.scales[m] = scaled ? static_cast<uint8_t*>(scales[m]) : nullptr;
     }
     a.staged = staged ? 1u : 0u;
-    return launch_fragment<kQuantize>(a, plan, p, vec, fmt, stream);
+    return launch_fragment<kQuantize>(a, plan, p, al, fmt, stream);
 }
 
 static int reduce_fragment(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
@@ -1364,17 +1453,18 @@ static int reduce_fragment(const sdl_plan_t* plan, uint32_t p, float* g_base, fl
     Args a;
     std::memset(&a, 0, sizeof(a));
     a.g = g_base; a.mom = mom_base; a.M = M; a.lr = lr; a.mu = mu;
-    bool vec = aligned(g_base, 16) && aligned(mom_base, 16);
+    Align16 al;
+    al.model = aligned(g_base, 16) && aligned(mom_base, 16);
     for (uint32_t m = 0; m < M; ++m) {
         if (!codes[m] || (scaled && !scales[m])) return SDL_ERR_INVALID_ARG;
         if (!aligned(codes[m], code_align(fmt))) return SDL_ERR_ALIGNMENT;
         if (scaled && !aligned(scales[m], scale_align(fmt))) return SDL_ERR_ALIGNMENT;
-        vec = vec && aligned(codes[m], 16);
+        al.msg = al.msg && aligned(codes[m], 16);
         a.codes[m] = static_cast<uint8_t*>(const_cast<void*>(codes[m]));
         a.scales[m] = scaled ? static_cast<uint8_t*>(const_cast<void*>(scales[m])) : nullptr;
     }
     a.staged = staged ? 1u : 0u;
-    return launch_fragment<kReduce>(a, plan, p, vec, fmt, stream);
+    return launch_fragment<kReduce>(a, plan, p, al, fmt, stream);
 }
 
 static int receive_fragment(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
@@ -1383,11 +1473,11 @@ static int receive_fragment(const sdl_plan_t* plan, uint32_t p, float* g_base, f
 {
     if (!plan || p >= sdl_plan_num_fragments(plan)) return SDL_ERR_INVALID_ARG;
     Args a;
-    bool vec = false;
-    int rc = fill_receive_args(a, g_base, mom_base, codes, scales, w_now_base, M, fmt, lr, mu, alpha, &vec);
+    Align16 al;
+    int rc = fill_receive_args(a, g_base, mom_base, codes, scales, w_now_base, M, fmt, lr, mu, alpha, &al);
     if (rc != SDL_OK) return rc;
     a.staged = staged ? 1u : 0u;
-    return launch_fragment<kReceive>(a, plan, p, vec, fmt, stream);
+    return launch_fragment<kReceive>(a, plan, p, al, fmt, stream);
 }
 
 static int merge_fragment(const sdl_plan_t* plan, uint32_t p, const float* g_new_base, void* const* w_now_base,
@@ -1399,15 +1489,16 @@ static int merge_fragment(const sdl_plan_t* plan, uint32_t p, const float* g_new
     Args a;
     std::memset(&a, 0, sizeof(a));
     a.g = const_cast<float*>(g_new_base); a.M = M; a.alpha = alpha; a.one_minus_alpha = 1.0f - alpha;
-    bool vec = aligned(g_new_base, 16);
+    Align16 al;
+    al.model = aligned(g_new_base, 16);
     for (uint32_t m = 0; m < M; ++m) {
         if (!w_now_base[m]) return SDL_ERR_INVALID_ARG;
         if (!aligned(w_now_base[m], 2)) return SDL_ERR_ALIGNMENT;
-        vec = vec && aligned(w_now_base[m], 16);
+        al.model = al.model && aligned(w_now_base[m], 16);
         a.w_now[m] = static_cast<uint16_t*>(w_now_base[m]);
     }
     a.staged = staged ? 1u : 0u;
-    return launch_fragment<kMerge>(a, plan, p, vec, SDL_FMT_FP32, stream);
+    return launch_fragment<kMerge>(a, plan, p, al, SDL_FMT_FP32, stream);
 }
 
 

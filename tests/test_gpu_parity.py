@@ -162,13 +162,46 @@ def test_fused_equals_three_calls_on_gpu(fmt):
 
 
 @pytest.mark.parametrize("fmt", FMTS)
-def test_unaligned_pointers_take_the_slow_path(fmt):
-    """Arrays that start at odd element offsets (4-byte / 2-byte aligned only)."""
+def test_unaligned_model_arrays(fmt):
+    """Model arrays that start at odd element offsets (4-byte / 2-byte aligned only): whole tiles
+    go through element-aligned vectors, the ragged last tile element by element."""
     n, M = 2 * 2048 + 5, 2
     g, mom, w_send, w_now = _span(n + 3, M, tau=1)
     views = (g[1:1 + n], mom[3:3 + n], [w[1:1 + n] for w in w_send], [w[3:3 + n] for w in w_now])
     assert views[0].data_ptr() % 16 != 0 and views[2][0].data_ptr() % 16 != 0
     check_fused_against_oracle(*views, fmt, LR, MU, 0.5, emit=True, what=f"unaligned fmt={fmt}")
+
+
+@pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("model_offset", [0, 1])
+def test_unaligned_message_arrays(fmt, model_offset):
+    """Message arrays at the smallest alignment their element type allows (1 byte for the 4- and
+    8-bit codes, 2 / 4 bytes for bf16 / fp32): every tile goes element by element."""
+    n, M = 3 * 512 + 77, 2
+    g0, mom0, ws0, wn0 = _span(n + 1, M, tau=1, delta="student_t3")
+    o = model_offset
+    g, mom = g0[o:o + n], mom0[o:o + n]
+    w_send, w_now = [w[o:o + n] for w in ws0], [w[o:o + n] for w in wn0]
+    ref = HostCopy(g, mom, w_send, w_now)
+    cb, sb = sdl.sdl_exchange_bytes(fmt, n)
+    step = {sdl.FMT_FP32: 4, sdl.FMT_BF16: 2}.get(fmt, 1)
+    code_bufs = [torch.zeros(cb + 16, dtype=torch.uint8, device=DEV) for _ in range(M)]
+    codes = [b[step:] for b in code_bufs]
+    assert codes[0].data_ptr() % 16 == step
+    scales = sdl.alloc_exchange(fmt, n, M)[1]
+    sdl.sdl_quantize_outer_grad(g, w_send, n, fmt, codes, scales)
+    sdl.sdl_receive_outer_step(g, mom, codes, scales, w_now, n, fmt, LR, MU, 0.5)
+    torch.cuda.synchronize()
+    rc, rs = oracle.fragment_outer_step(ref.g, ref.mom, ref.w_send, ref.w_now, fmt, LR, MU, 0.5, want_codes=True)
+    for m in range(M):
+        assert_bytes_equal(codes[m][:cb].cpu().numpy(), rc[m], f"codes[{m}]")
+        if sb:
+            assert_bytes_equal(scales[m][:sb].cpu().numpy(), rs[m], f"scales[{m}]")
+        assert code_bufs[m][:step].sum() == 0 and code_bufs[m][step + cb:].sum() == 0
+    assert_f32_close(host_f32(g), ref.g, "g")
+    assert_f32_close(host_f32(mom), ref.mom, "mom")
+    for m in range(M):
+        assert_bf16_within_ulp(host_bits(w_now[m]), ref.w_now[m], f"w_now[{m}]")
 
 
 def _from_host(g, mom, w_send, w_now):
