@@ -134,6 +134,14 @@ int sdl_fragment_plan(const uint64_t* unit_numel, const int32_t* unit_block, uin
  * per fragment give 8 / 16 / 36 block fragments and a synchronisation every 11 / 5 / 2 steps,
  * i.e. H / (fragments + 1)). */
 #define SDL_PLAN_PRE_OWN_FRAGMENT 1u
+/* SDL_PLAN_ALIGN_GROUPS (a memory-layout option, not part of the method): every parameter group
+ * starts at the next multiple of SDL_PLAN_GROUP_ALIGN elements of the flat arrays, i.e. on a
+ * 128-byte boundary of the bf16 replicas when their bases are 128-byte aligned, which is what
+ * the kernels need for full speed whatever the group sizes are.  The spans' offsets and
+ * sdl_plan_total_numel then include the padding; padding elements belong to no fragment and
+ * are never read or written.  The caller lays its flat arrays out by the spans' offsets. */
+#define SDL_PLAN_ALIGN_GROUPS 2u
+#define SDL_PLAN_GROUP_ALIGN 64u
 int sdl_fragment_plan_ex(const uint64_t* unit_numel, const int32_t* unit_block, uint32_t n_units,
                          uint32_t n_blocks, uint32_t P, sdl_pattern_t pattern, uint32_t H, uint32_t tau,
                          const uint32_t* t_p, uint32_t flags, sdl_plan_t** out);

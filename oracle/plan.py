@@ -61,10 +61,13 @@ class RefPlan:
 
 def fragment_plan(unit_numel: Sequence[int], unit_block: Sequence[int], n_blocks: int, P: int,
                   pattern: int, H: int, tau: int, t_p: Optional[Sequence[int]] = None,
-                  pre_own_fragment: bool = False) -> RefPlan:
+                  pre_own_fragment: bool = False, align: int = 1) -> RefPlan:
     """pre_own_fragment: the embedding (UNIT_PRE) is a fragment of its own, number 0, and the
     blocks use fragments 1..P -- the reading under which the appendix's "8, 16, 36 fragments,
-    one synchronised every 11, 5, 2 steps" adds up (H / (fragments + 1))."""
+    one synchronised every 11, 5, 2 steps" adds up (H / (fragments + 1)).
+
+    align: a memory-layout option, not part of the method: every parameter group starts at the
+    next multiple of `align` elements; the padding in between belongs to no fragment."""
     assert 1 <= P <= n_blocks and H >= 1 and 0 <= tau < H
     shift = 1 if pre_own_fragment else 0
     block_fragment = []
@@ -82,6 +85,8 @@ def fragment_plan(unit_numel: Sequence[int], unit_block: Sequence[int], n_blocks
     spans = [[] for _ in range(P)]
     pos = 0
     for u, (numel, blk) in enumerate(zip(unit_numel, unit_block)):
+        while pos % align != 0:
+            pos += 1
         if blk == UNIT_PRE:
             p = 0 if pre_own_fragment else block_fragment[0]
         elif blk == UNIT_POST:

@@ -181,6 +181,8 @@ class Plan:
 
 
 PLAN_PRE_OWN_FRAGMENT = 1
+PLAN_ALIGN_GROUPS = 2
+PLAN_GROUP_ALIGN = 64
 
 
 def sdl_fragment_plan_ex(unit_numel: Sequence[int], unit_block: Sequence[int], n_blocks: int, P: int,

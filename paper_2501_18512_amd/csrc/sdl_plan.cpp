@@ -64,7 +64,7 @@ int sdl_fragment_plan_ex(const uint64_t* unit_numel, const int32_t* unit_block, 
                          const uint32_t* t_p, uint32_t flags, sdl_plan_t** out)
 {
     if (!out || (n_units && (!unit_numel || !unit_block))) return SDL_ERR_INVALID_ARG;
-    if (flags & ~(uint32_t)SDL_PLAN_PRE_OWN_FRAGMENT) return SDL_ERR_INVALID_ARG;
+    if (flags & ~(uint32_t)(SDL_PLAN_PRE_OWN_FRAGMENT | SDL_PLAN_ALIGN_GROUPS)) return SDL_ERR_INVALID_ARG;
     // with the flag, fragment 0 holds the SDL_UNIT_PRE groups alone and the blocks use 1..P
     const uint32_t shift = (flags & SDL_PLAN_PRE_OWN_FRAGMENT) ? 1u : 0u;
     const uint32_t n_frag = P + shift;
@@ -97,6 +97,8 @@ int sdl_fragment_plan_ex(const uint64_t* unit_numel, const int32_t* unit_block, 
             if (b == SDL_UNIT_PRE) owner = shift ? 0u : plan->block_owner[0];
             else if (b == SDL_UNIT_POST) owner = plan->block_owner[n_blocks - 1];
             else owner = plan->block_owner[(uint32_t)b];
+            if (flags & SDL_PLAN_ALIGN_GROUPS)
+                pos = (pos + SDL_PLAN_GROUP_ALIGN - 1) / SDL_PLAN_GROUP_ALIGN * SDL_PLAN_GROUP_ALIGN;
             sdl_span_t s;
             s.offset = pos; s.numel = unit_numel[u]; s.unit = (int32_t)u;
             plan->spans[owner].push_back(s);

@@ -1,7 +1,8 @@
 """Seeded random sweep of the fragment-level fused call against the oracle: random models
 (number and sizes of parameter groups, ragged and block-aligned, blocks, embedding/head groups),
-fragment count and pattern, format, replica count, aliasing, flat or staged outer state, messages
-written or not.  The oracle walks the parameter groups of its own plan one by one."""
+fragment count and pattern, layout with or without padding, format, replica count, aliasing, flat
+or staged outer state, messages written or not.  The oracle walks the parameter groups of its own
+plan one by one."""
 import os
 
 import numpy as np
@@ -67,13 +68,16 @@ def test_random_fragment_level_fused_calls(chunk):
         M = int(rng.choice([1, 2, 3, 4, 8, 9]))
         tau = int(rng.integers(0, 2))
         emit, staged = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+        padded = bool(rng.integers(0, 2))            # groups laid out on 64-element boundaries
         lr, mu, alpha = float(rng.choice([0.4, 0.7])), float(rng.choice([0.0, 0.9])), float(rng.choice([0.0, 0.5, 1.0]))
         seed = int(rng.integers(1 << 30))
         print(f"random plan case {chunk}.{i}: units={len(numel)} L={L} P={P} pattern={pattern} own={own} "
-              f"fmt={fmt} M={M} tau={tau} emit={emit} staged={staged} seed={seed}", flush=True)
+              f"fmt={fmt} M={M} tau={tau} emit={emit} staged={staged} padded={padded} seed={seed}", flush=True)
         plan = sdl.sdl_fragment_plan_ex(numel, block, L, P, pattern, 10, tau,
-                                        flags=sdl.PLAN_PRE_OWN_FRAGMENT if own else 0)
-        ref_plan = oracle.fragment_plan(numel, block, L, P, pattern, 10, tau, pre_own_fragment=own)
+                                        flags=(sdl.PLAN_PRE_OWN_FRAGMENT if own else 0)
+                                        | (sdl.PLAN_ALIGN_GROUPS if padded else 0))
+        ref_plan = oracle.fragment_plan(numel, block, L, P, pattern, 10, tau, pre_own_fragment=own,
+                                        align=sdl.PLAN_GROUP_ALIGN if padded else 1)
         total = plan.total_numel
         assert total == ref_plan.total
         g, mom, w_send, w_now = workloads.make_span(total, M, tau=tau, delta="student_t3", base_seed=seed,

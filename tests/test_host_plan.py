@@ -4,6 +4,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 import oracle
@@ -81,9 +82,24 @@ def test_plan_with_embedding_fragment_matches_oracle(shape, P, pattern, H):
     for t in range(1, 2 * H + 3):
         assert sdl.sdl_plan_events(plan, t) == (ref.sends(t), ref.receives(t))
     with pytest.raises(sdl.SdlError):
-        sdl.sdl_fragment_plan_ex(numel, block, L, P, pattern, H, 1, flags=2)
+        sdl.sdl_fragment_plan_ex(numel, block, L, P, pattern, H, 1, flags=4)
     with pytest.raises(sdl.SdlError):
         sdl.sdl_fragment_plan_ex(numel, block, L, P, pattern, H, 1, t_p=[0] * P, flags=sdl.PLAN_PRE_OWN_FRAGMENT)
+
+
+def test_aligned_layout_matches_oracle():
+    rng = np.random.default_rng(11)
+    numel = [int(x) for x in rng.integers(0, 700, 60)] + [64, 128, 1, 4096]
+    block = [sdl.UNIT_PRE] + [int(x) for x in rng.integers(0, 5, 59)] + [4, 4, sdl.UNIT_POST, sdl.UNIT_POST]
+    for flags, own in ((sdl.PLAN_ALIGN_GROUPS, False), (sdl.PLAN_ALIGN_GROUPS | sdl.PLAN_PRE_OWN_FRAGMENT, True)):
+        ref = oracle.fragment_plan(numel, block, 5, 3, sdl.PATTERN_STRIDED, 20, 2, pre_own_fragment=own,
+                                   align=sdl.PLAN_GROUP_ALIGN)
+        plan = sdl.sdl_fragment_plan_ex(numel, block, 5, 3, sdl.PATTERN_STRIDED, 20, 2, flags=flags)
+        assert plan.total_numel == ref.total
+        for p in range(ref.P):
+            assert sdl.sdl_plan_fragment_spans(plan, p) == ref.spans[p]
+            for off, n, _ in sdl.sdl_plan_fragment_runs(plan, p):
+                assert off % sdl.PLAN_GROUP_ALIGN == 0           # every run starts on a boundary
 
 
 def test_runs_respect_ragged_spans():

@@ -88,6 +88,20 @@ def test_decoder_shapes_partition_exactly(name, P, sizes, total):
     assert all(n % 32 == 0 for _, n, _ in allspans)
 
 
+def test_aligned_layout_pads_to_the_next_boundary_and_no_further():
+    """The layout option moves nothing between fragments; every group starts on a multiple of the
+    alignment, directly behind its predecessor's last element rounded up, and the sizes are kept."""
+    numel = [5, 64, 0, 63, 65, 128, 1, 1, 200]
+    block = [-1, 0, 0, 1, 1, 2, 2, -2, -2]
+    plain = fragment_plan(numel, block, 3, 3, PATTERN_STRIDED, 10, 1)
+    padded = fragment_plan(numel, block, 3, 3, PATTERN_STRIDED, 10, 1, align=64)
+    assert [[(n, u) for _, n, u in f] for f in padded.spans] == [[(n, u) for _, n, u in f] for f in plain.spans]
+    by_unit = sorted((u, off, n) for f in padded.spans for off, n, u in f)
+    assert [off for _, off, _ in by_unit] == [0, 64, 128, 128, 192, 320, 448, 512, 576]   # worked by hand
+    assert padded.total == 576 + 200 and plain.total == sum(numel)
+    assert fragment_plan(numel, block, 3, 3, PATTERN_STRIDED, 10, 1, align=1).spans == plain.spans
+
+
 def test_colliding_offsets_all_reported():
     plan = fragment_plan(*_blocks_only(4), 4, 4, PATTERN_STRIDED, 100, 30, t_p=[0, 0, 30, 60])
     assert plan.sends(100) == [0, 1]

@@ -27,6 +27,9 @@ MISTAKES = [
     ("the own-fragment variant keeps the embedding with block 0", "            p = 0 if pre_own_fragment else block_fragment[0]",
      "            p = block_fragment[0]"),
     ("spans do not advance through the model", "        pos += int(numel)", "        pos += 0"),
+    ("the aligned layout always inserts padding", "        while pos % align != 0:\n            pos += 1",
+     "        pos += 1\n        while pos % align != 0:\n            pos += 1"),
+    ("the aligned layout ignores the alignment", "        while pos % align != 0:\n            pos += 1", "        pass"),
 ]
 
 
