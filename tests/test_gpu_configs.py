@@ -82,6 +82,43 @@ def test_config_1b_fragment_sampled():
     assert torch.equal(before.view(torch.int32), model.g[o:o + n].view(torch.int32))
 
 
+def test_config_1b_send_then_receive_sampled():
+    """The two launches the schedule driver issues for a fragment when tau > 0 (send side, then the
+    one-pass receive side into the replicas as they are tau steps later), at full size: messages and
+    state on sampled windows against the oracle."""
+    wl = workloads.WORKLOADS["1b"]
+    fmt = sdl.FORMATS[wl.fmt]
+    model = FlatModel(wl, fill_fragments=[1])
+    runs = sdl.sdl_plan_fragment_runs(model.plan, 1)
+    wins = model.windows(1, n_random=16, seed=9)
+    snaps = model.snapshot(wins)
+    cb, sb = sdl.sdl_plan_message_bytes(model.plan, 1, fmt)
+    assert cb == 302014464 // 2 and sb == 302014464 // 32          # every run is a whole number of tiles
+    codes = [torch.zeros(cb, dtype=torch.uint8, device=DEV) for _ in range(wl.M)]
+    scales = [torch.zeros(sb, dtype=torch.uint8, device=DEV) for _ in range(wl.M)]
+    sdl.sdl_quantize_outer_grad_plan(model.plan, 1, model.g, model.w_send, fmt, codes, scales)
+    sdl.sdl_receive_outer_step_plan(model.plan, 1, model.g, model.mom, codes, scales, model.w_now, fmt,
+                                    wl.lr, wl.mu, wl.alpha)
+    torch.cuda.synchronize()
+    msg_start, pos = {}, 0
+    for off, n, _ in runs:
+        msg_start[off] = pos
+        pos += (n + 511) // 512 * 512
+    for (o, n), ref in zip(wins, snaps):
+        ro = max(q for q in msg_start if q <= o)
+        rel = msg_start[ro] + (o - ro)
+        rc, rs = oracle.quantize_outer_grad(ref.g, ref.w_send, fmt)
+        for m in range(wl.M):
+            assert_bytes_equal(codes[m][rel // 2:rel // 2 + len(rc[m])].cpu().numpy(), rc[m], f"codes[{m}] window@{o}")
+            assert_bytes_equal(scales[m][rel // 32:rel // 32 + len(rs[m])].cpu().numpy(), rs[m], f"scales[{m}] window@{o}")
+        oracle.dequant_reduce_nesterov(ref.g, ref.mom, rc, rs, fmt, wl.lr, wl.mu)
+        oracle.merge_overlap(ref.g, ref.w_now, wl.alpha)
+        assert_f32_close(host_f32(model.g[o:o + n]), ref.g, f"g window@{o}")
+        assert_f32_close(host_f32(model.mom[o:o + n]), ref.mom, f"mom window@{o}")
+        for m in range(wl.M):
+            assert_bf16_within_ulp(host_bits(model.w_now[m][o:o + n]), ref.w_now[m], f"w_now[{m}] window@{o}")
+
+
 @pytest.mark.parametrize("fmt", ["e3m0", "fp32"])
 def test_config_4b_p1_equals_p6(fmt):
     """The same seed synchronised as one fragment and as six strided fragments gives the same
