@@ -16,9 +16,10 @@
 //                     lane 0 writes one partial Gram matrix.  The next tile's loads are issued
 //                     before the current tile is consumed.
 //   sdl_gram_finalize adds the partial matrices of a set in a fixed order (lane-strided, then
-//                     the same butterfly) and derives cos and the mean over pairs.  The same
-//                     kernel adds the Gram matrices of several sets (fragment from spans,
-//                     unions of fragments).
+//                     the same butterfly; a set with more than 128 partial matrices in two
+//                     launches, chunks of 64 first) and derives cos and the mean over pairs.
+//                     The same kernel adds the Gram matrices of several sets (fragment from
+//                     spans, unions of fragments).
 // No atomics: the order of every sum depends on the sizes alone, so results are reproducible.
 // More than 8 replicas are handled as 8 x 8 blocks of the matrix, one launch per block.
 #include <hip/hip_runtime.h>
