@@ -28,11 +28,13 @@
 #include <cstdlib>
 
 #include "sdl.h"
+#include "sdl_device.h"
 
 namespace {
 
+using namespace sdl_device;
+
 constexpr int kLaneElems = 8;                   // consecutive parameters a lane owns in a tile
-constexpr int kWave = 64;
 constexpr int kTile = kLaneElems * kWave;       // 512
 constexpr int kBlockM = 8;                      // replicas per side of one launch's block of the matrix
 constexpr int kMaxSets = 48;                    // parameter sets per launch
@@ -44,8 +46,6 @@ constexpr uint32_t kMaxGroups = 8192;           // what the workspace is sized f
 #ifndef SDL_GRAM_PREFETCH
 #define SDL_GRAM_PREFETCH 1      // issue the next tile's loads before the current tile is consumed
 #endif
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 struct Set {
     uint64_t offset;     // first element in the flat arrays
@@ -76,23 +76,12 @@ struct GramArgs {
     Piece pieces[kMaxPieces];
 };
 
-__device__ __forceinline__ float u2f(uint32_t u) { return __builtin_bit_cast(float, u); }
-
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* p, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
-}
-
 // Raw bits of one tile as a lane holds them: 8 fp32 of g, 8 bf16 of each replica.
 template <int NW>
 struct TileRegs {
     u32x4 g0, g1;
     u32x4 w[NW];
 };
-
-// 16 bytes at the alignment of an fp32 / a bf16 element
-typedef uint32_t u32x4_f32elem __attribute__((ext_vector_type(4), aligned(4)));
-typedef uint32_t u32x4_bf16elem __attribute__((ext_vector_type(4), aligned(2)));
 
 // valid = parameters of the tile that exist (512 except in a set's last tile).  Full tiles of
 // aligned sets use 128-bit buffer loads, full tiles of sets that start at some other element

@@ -3,22 +3,21 @@
 // model's storage type (bf16).  One streaming pass for gfx950: a workgroup is one 64-lane
 // wavefront and owns a tile of 512 consecutive parameters; lane l reads and writes the eight
 // parameters [8l, 8l+8) -- one 128-bit access per bf16 array, two per fp32 array, non-temporal.
-// Ragged tails and unaligned arrays go element by element under the buffer range check.
+// Whole tiles of arrays that start at any other element go through 128-bit accesses of element
+// alignment, ragged tails element by element under the buffer range check.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
 
 #include "sdl.h"
+#include "sdl_device.h"
 
 namespace {
 
-constexpr int kLaneElems = 8;
-constexpr int kWave = 64;
-constexpr int kTile = kLaneElems * kWave;
+using namespace sdl_device;
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2_t __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+constexpr int kLaneElems = 8;
+constexpr int kTile = kLaneElems * kWave;
 
 struct EvalArgs {
     const float* g;
@@ -30,23 +29,12 @@ struct EvalArgs {
     uint32_t fast;       // every array that is touched is 16-byte aligned
 };
 
-__device__ __forceinline__ float u2f(uint32_t u) { return __builtin_bit_cast(float, u); }
-
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* p, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
-}
-
 // two fp32 -> two bf16 (round to nearest even) in one 32-bit word, first value in the low half
 __device__ __forceinline__ uint32_t bf16_pack(float lo, float hi)
 {
     const f32x2_t v = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
-
-// 16 bytes at the alignment of an fp32 / a bf16 element
-typedef uint32_t u32x4_f32elem __attribute__((ext_vector_type(4), aligned(4)));
-typedef uint32_t u32x4_bf16elem __attribute__((ext_vector_type(4), aligned(2)));
 
 // The lane's 8 bf16 of one array as 4 words (element 2k in the low half of word k): a 128-bit
 // buffer access in a whole tile when every array is 16-byte aligned, a 128-bit access of element

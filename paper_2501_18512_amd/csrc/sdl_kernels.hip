@@ -33,13 +33,15 @@
 #include <vector>
 
 #include "sdl.h"
+#include "sdl_device.h"
 
 namespace {
 
+using namespace sdl_device;
+
 constexpr int kVec = 4;                       // consecutive parameters a lane owns in one row
 constexpr int kRows = 2;                      // rows of a tile
-constexpr int kWave = 64;                     // lanes per workgroup: one wavefront
-constexpr int kRow = kVec * kWave;            // parameters per row (256)
+constexpr int kRow = kVec * kWave;            // parameters per row (256); a workgroup is one wavefront
 constexpr int kGroup = kRow * kRows;          // parameters per workgroup tile (512)
 constexpr int kMaxRuns = 16;                  // runs per launch
 
@@ -103,15 +105,7 @@ struct Args {
 #define SDL_WAVES_PER_EU 2   // register budget: at least this many wavefronts per SIMD
 #endif
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2_t __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-
 // ------------------------------------------------------------------ bit helpers
-
-__device__ __forceinline__ uint32_t f2u(float x) { return __builtin_bit_cast(uint32_t, x); }
-__device__ __forceinline__ float u2f(uint32_t u) { return __builtin_bit_cast(float, u); }
 
 // bf16 pair packed in one dword: element 0 in the low half.
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return u2f(u << 16); }
@@ -312,10 +306,6 @@ __device__ __forceinline__ void decode_e4m3(uint32_t c0, float scale, float (&dq
 //   GuardedIO  any alignment, any tail: per-element global loads / stores under a
 //              per-row count of valid elements
 
-// vectors of element alignment: the compiler picks the widest access the target allows
-typedef float f32x4_elem __attribute__((ext_vector_type(4), aligned(4)));
-typedef uint32_t u32x2_elem __attribute__((ext_vector_type(2), aligned(2)));
-
 template <bool ALIGNED>
 struct TileIOT {
     const Args& a;
@@ -325,10 +315,6 @@ struct TileIOT {
     uint32_t sidx;    // whole-span scale: index of the run's scale word
     uint64_t s0;      // tile's first element in g / mom (= t0 unless the state is staged)
 
-    static __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* p, uint32_t bytes)
-    {
-        return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
-    }
     // bit pattern of the span's absolute maximum (whole-span scale)
     __device__ __forceinline__ uint32_t span_amax(uint32_t m) const
     {
@@ -815,10 +801,6 @@ struct AbsmaxArgs {
     AbsmaxRun runs[kAbsmaxMaxRuns];
 };
 
-// 16 bytes at the alignment of an fp32 / a bf16 element
-typedef uint32_t u32x4_f32elem __attribute__((ext_vector_type(4), aligned(4)));
-typedef uint32_t u32x4_bf16elem __attribute__((ext_vector_type(4), aligned(2)));
-
 template <int MB>
 struct AbsmaxTile {
     u32x4 g0, g1;
@@ -830,12 +812,12 @@ __device__ __forceinline__ void absmax_load(AbsmaxTile<MB>& t, const AbsmaxArgs&
                                             uint32_t valid, bool fast, uint32_t lane)
 {
     if (fast && valid == (uint32_t)kGroup) {
-        const __amdgpu_buffer_rsrc_t rg = TileIO::rsrc(a.g + ge, kGroup * 4);
+        const __amdgpu_buffer_rsrc_t rg = rsrc(a.g + ge, kGroup * 4);
         t.g0 = __builtin_amdgcn_raw_buffer_load_b128(rg, (int)(lane * 32), 0, SDL_AUX_LD);
         t.g1 = __builtin_amdgcn_raw_buffer_load_b128(rg, (int)(lane * 32 + 16), 0, SDL_AUX_LD);
 #pragma unroll
         for (int m = 0; m < MB; ++m)
-            t.w[m] = __builtin_amdgcn_raw_buffer_load_b128(TileIO::rsrc(a.w_send[a.m0 + m] + we, kGroup * 2),
+            t.w[m] = __builtin_amdgcn_raw_buffer_load_b128(rsrc(a.w_send[a.m0 + m] + we, kGroup * 2),
                                                            (int)(lane * 16), 0, SDL_AUX_LD);
     } else if (valid == (uint32_t)kGroup) {
         // a whole tile of a run that starts at some other element: vectors of element alignment
@@ -849,7 +831,7 @@ __device__ __forceinline__ void absmax_load(AbsmaxTile<MB>& t, const AbsmaxArgs&
     } else {
         // ragged tail: element by element under the buffer range check, which returns 0 past the
         // end (g = 0 and w = 0 give an outer gradient of 0: no effect on a maximum)
-        const __amdgpu_buffer_rsrc_t rg = TileIO::rsrc(a.g + ge, valid * 4);
+        const __amdgpu_buffer_rsrc_t rg = rsrc(a.g + ge, valid * 4);
         uint32_t x[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) x[j] = __builtin_amdgcn_raw_buffer_load_b32(rg, (int)((lane * 8 + j) * 4), 0, 0);
@@ -857,7 +839,7 @@ __device__ __forceinline__ void absmax_load(AbsmaxTile<MB>& t, const AbsmaxArgs&
         t.g1 = u32x4{x[4], x[5], x[6], x[7]};
 #pragma unroll
         for (int m = 0; m < MB; ++m) {
-            const __amdgpu_buffer_rsrc_t rw = TileIO::rsrc(a.w_send[a.m0 + m] + we, valid * 2);
+            const __amdgpu_buffer_rsrc_t rw = rsrc(a.w_send[a.m0 + m] + we, valid * 2);
             uint32_t h[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j)
