@@ -2,8 +2,8 @@
 // gfx950 (MI355X), and the C entry points that launch them.
 //
 // One templated kernel serves every call: send side (quantize), receive side (decode + mean +
-// Nesterov, with or without the merge), merge alone, the fused outer step, and the
-// absolute-maximum pre-pass of the whole-span scale.
+// Nesterov, with or without the merge), merge alone, and the fused outer step; the
+// absolute-maximum pre-pass of the whole-span scale is a kernel of its own.
 //
 // Work decomposition (all modes).  A workgroup is one 64-lane wavefront and owns a
 // tile of 512 consecutive parameters, seen as two rows of 256.  Lane l owns the four
@@ -15,8 +15,9 @@
 //     is three DPP exchanges (two inside the quad, one across the half row); wider
 //     blocks add a row mirror and ds_bpermute exchanges.  No LDS storage is used.
 // Full, 16-byte aligned tiles use buffer instructions with non-temporal cache policy
-// (every byte is touched once); ragged tails and unaligned runs use guarded
-// element-wise accesses.  A launch covers up to kMaxRuns contiguous runs of the flat
+// (every byte is touched once); full tiles of runs whose model arrays start at some other
+// element use vector accesses of element alignment in the same lane layout; ragged tails
+// and calls with unaligned message arrays use guarded element-wise accesses.  A launch covers up to kMaxRuns contiguous runs of the flat
 // model; every workgroup belongs to exactly one run, so scale blocks never straddle
 // runs.
 //
