@@ -41,12 +41,36 @@ namespace {
 using namespace sdl_device;
 
 constexpr int kVec = 4;                       // consecutive parameters a lane owns in one row
-constexpr int kRows = 2;                      // rows of a tile
+constexpr int kMaxRows = 2;                   // rows of the tallest tile
 constexpr int kRow = kVec * kWave;            // parameters per row (256); a workgroup is one wavefront
-constexpr int kGroup = kRow * kRows;          // parameters per workgroup tile (512)
+constexpr int kPad = kRow * kMaxRows;          // message and staging layouts pad every piece to this many
+                                              // parameters (512): a whole number of tiles of either height
 constexpr int kMaxRuns = 16;                  // runs per launch
 
 enum Mode { kQuantize = 0, kReduce = 1, kMerge = 2, kFused = 3, kReceive = 5 };   // kReceive = kReduce + kMerge
+
+// Rows of a workgroup's tile, by call and compile-time replica count (0 = any M at run time).
+// Rows are independent of each other (a scale block never leaves its row), so the height is a
+// pure scheduling choice.  Measured on MI355X over 302 M parameters: one row instead of two gains
+// 1-3 % on the fused kernel and the one-pass receive at M = 2 and 4 and 2-8 % on the receive side
+// without the merge, and loses 2 % on the first two at M = 8, 1-3 % on the merge and 3-7 % on the
+// send side.  The whole-span scale keeps two rows: every tile reads its span's scale words, all
+// tiles of a span the same few bytes, and twice the tiles cost it 8-14 %.
+constexpr int tile_rows(int mode, int mt, int fmt)
+{
+    if (fmt == SDL_FMT_E3M0_SPAN) return 2;
+    if (mode == kReduce) return (mt == 2 || mt == 4 || mt == 8) ? 1 : 2;
+    if (mode == kFused || mode == kReceive) return (mt == 2 || mt == 4) ? 1 : 2;
+    return 2;
+}
+// The compile-time replica count a call runs with: the kernels are built for 1, 2, 4 and 8 replicas
+// plus one variant that takes any M; the message-writing fused kernel is a verification aid, for
+// which the any-M variant is enough.
+constexpr uint32_t variant_mt(int mode, uint32_t M, bool emit)
+{
+    const uint32_t mt = (mode == kFused && emit) ? 0u : M;
+    return (mt == 1 || mt == 2 || mt == 4 || mt == 8) ? mt : 0u;
+}
 
 constexpr bool is_e3m0(int f) { return f == SDL_FMT_E3M0 || f >= SDL_FMT_E3M0_B64; }
 constexpr bool is_scaled(int f) { return f == SDL_FMT_E4M3 || is_e3m0(f); }
@@ -307,8 +331,9 @@ __device__ __forceinline__ void decode_e4m3(uint32_t c0, float scale, float (&dq
 //   GuardedIO  any alignment, any tail: per-element global loads / stores under a
 //              per-row count of valid elements
 
-template <bool ALIGNED>
+template <bool ALIGNED, int ROWS>
 struct TileIOT {
+    static constexpr int kTile = ROWS * kRow;   // parameters of the tile
     const Args& a;
     uint64_t t0;      // tile's first element in the flat arrays (workgroup uniform)
     uint64_t tb;      // tile's first element in the message arrays (a multiple of 512)
@@ -328,7 +353,7 @@ struct TileIOT {
         } else {
             constexpr int B = block_elems(FMT);
             const uint32_t sb = __builtin_amdgcn_raw_buffer_load_b8(
-                rsrc(a.scales[m] + tb / B, kGroup / B), (int)(row * (kRow / B) + lane / (B / kVec)), 0, SDL_AUX_SCALE);
+                rsrc(a.scales[m] + tb / B, kTile / B), (int)(row * (kRow / B) + lane / (B / kVec)), 0, SDL_AUX_SCALE);
             return scale_from_byte(sb);
         }
     }
@@ -337,33 +362,33 @@ struct TileIOT {
         if constexpr (!is_span_scaled(FMT)) {
             constexpr int B = block_elems(FMT);
             if ((lane % (B / kVec)) == 0u)
-                __builtin_amdgcn_raw_buffer_store_b8((uint8_t)sb, rsrc(a.scales[m] + tb / B, kGroup / B),
+                __builtin_amdgcn_raw_buffer_store_b8((uint8_t)sb, rsrc(a.scales[m] + tb / B, kTile / B),
                                                      (int)(row * (kRow / B) + lane / (B / kVec)), 0, SDL_AUX_SCALE);
         }
     }
     // p = address of the tile's first element in the array
     __device__ __forceinline__ void ld_f32(const float* p, int row, float (&v)[kVec]) const
     {
-        const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rsrc(p, kGroup * 4),
+        const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rsrc(p, kTile * 4),
                                                               (int)(row * kRow * 4 + lane * 16), 0, SDL_AUX_LD);
         v[0] = u2f(x.x); v[1] = u2f(x.y); v[2] = u2f(x.z); v[3] = u2f(x.w);
     }
     __device__ __forceinline__ void st_f32(float* p, int row, const float (&v)[kVec]) const
     {
         const u32x4 x = {f2u(v[0]), f2u(v[1]), f2u(v[2]), f2u(v[3])};
-        __builtin_amdgcn_raw_buffer_store_b128(x, rsrc(p, kGroup * 4), (int)(row * kRow * 4 + lane * 16), 0,
+        __builtin_amdgcn_raw_buffer_store_b128(x, rsrc(p, kTile * 4), (int)(row * kRow * 4 + lane * 16), 0,
                                                SDL_AUX_ST);
     }
     __device__ __forceinline__ void ld_bf16(const uint16_t* p, int row, uint32_t (&u)[2]) const
     {
-        const u32x2 x = __builtin_amdgcn_raw_buffer_load_b64(rsrc(p, kGroup * 2),
+        const u32x2 x = __builtin_amdgcn_raw_buffer_load_b64(rsrc(p, kTile * 2),
                                                              (int)(row * kRow * 2 + lane * 8), 0, SDL_AUX_LD);
         u[0] = x.x; u[1] = x.y;
     }
     __device__ __forceinline__ void st_bf16(uint16_t* p, int row, const uint32_t (&u)[2]) const
     {
         const u32x2 x = {u[0], u[1]};
-        __builtin_amdgcn_raw_buffer_store_b64(x, rsrc(p, kGroup * 2), (int)(row * kRow * 2 + lane * 8), 0,
+        __builtin_amdgcn_raw_buffer_store_b64(x, rsrc(p, kTile * 2), (int)(row * kRow * 2 + lane * 8), 0,
                                               SDL_AUX_ST);
     }
 
@@ -430,12 +455,12 @@ struct TileIOT {
         } else {
             const float scale = load_scale<FMT>(m, row);
             if constexpr (is_e3m0(FMT)) {
-                const uint32_t c0 = __builtin_amdgcn_raw_buffer_load_b16(rsrc(codes + tb / 2, kGroup / 2),
+                const uint32_t c0 = __builtin_amdgcn_raw_buffer_load_b16(rsrc(codes + tb / 2, kTile / 2),
                                                                          (int)(row * (kRow / 2) + lane * 2), 0,
                                                                          SDL_AUX_LD);
                 decode_e3m0(c0, scale, dq);
             } else {
-                const uint32_t c0 = __builtin_amdgcn_raw_buffer_load_b32(rsrc(codes + tb, kGroup),
+                const uint32_t c0 = __builtin_amdgcn_raw_buffer_load_b32(rsrc(codes + tb, kTile),
                                                                          (int)(row * kRow + lane * 4), 0, SDL_AUX_LD);
                 decode_e4m3<EXACT>(c0, scale, dq);
             }
@@ -447,26 +472,24 @@ struct TileIOT {
         uint8_t* codes = a.codes[m];
         if constexpr (FMT == SDL_FMT_FP32) {
             const u32x4 x = {c[0], c[1], c[2], c[3]};
-            __builtin_amdgcn_raw_buffer_store_b128(x, rsrc(codes + tb * 4, kGroup * 4),
+            __builtin_amdgcn_raw_buffer_store_b128(x, rsrc(codes + tb * 4, kTile * 4),
                                                    (int)(row * kRow * 4 + lane * 16), 0, SDL_AUX_ST);
         } else if constexpr (FMT == SDL_FMT_BF16) {
             const u32x2 x = {c[0], c[1]};
-            __builtin_amdgcn_raw_buffer_store_b64(x, rsrc(codes + tb * 2, kGroup * 2),
+            __builtin_amdgcn_raw_buffer_store_b64(x, rsrc(codes + tb * 2, kTile * 2),
                                                   (int)(row * kRow * 2 + lane * 8), 0, SDL_AUX_ST);
         } else {
             store_scale<FMT>(m, row, sb);
             if constexpr (is_e3m0(FMT)) {
-                __builtin_amdgcn_raw_buffer_store_b16((uint16_t)c[0], rsrc(codes + tb / 2, kGroup / 2),
+                __builtin_amdgcn_raw_buffer_store_b16((uint16_t)c[0], rsrc(codes + tb / 2, kTile / 2),
                                                       (int)(row * (kRow / 2) + lane * 2), 0, SDL_AUX_ST);
             } else {
-                __builtin_amdgcn_raw_buffer_store_b32(c[0], rsrc(codes + tb, kGroup), (int)(row * kRow + lane * 4), 0,
+                __builtin_amdgcn_raw_buffer_store_b32(c[0], rsrc(codes + tb, kTile), (int)(row * kRow + lane * 4), 0,
                                                       SDL_AUX_ST);
             }
         }
     }
 };
-
-using TileIO = TileIOT<true>;
 
 struct GuardedIO {
     const Args& a;
@@ -601,7 +624,7 @@ struct GuardedIO {
 
 // ALIASED: w_send[m] and w_now[m] are the same array (no overlap delay).  EMIT: the fused
 // kernel also writes the messages.
-template <int MODE, int FMT, int MT, bool ALIASED, bool EMIT, class IO>
+template <int MODE, int FMT, int MT, bool ALIASED, bool EMIT, int kRows, class IO>
 __device__ __forceinline__ void process(const Args& a, const IO& io)
 {
     const uint32_t M = MT > 0 ? (uint32_t)MT : a.M;
@@ -751,20 +774,22 @@ void sdl_kernel(const Args a)
         if (wg >= a.runs[i].first_wg) r = i;
     const uint64_t run_off = a.runs[r].offset;
     const uint64_t run_n = a.runs[r].numel;
-    const uint64_t tile = (uint64_t)(wg - a.runs[r].first_wg) * kGroup;   // first element of the tile in the run
-    const bool whole = run_n - tile >= (uint64_t)kGroup;
+    constexpr int ROWS = tile_rows(MODE, MT, FMT);
+    constexpr int kTile = ROWS * kRow;
+    const uint64_t tile = (uint64_t)(wg - a.runs[r].first_wg) * kTile;   // first element of the tile in the run
+    const bool whole = run_n - tile >= (uint64_t)kTile;
     if (whole && a.runs[r].path == kPathBuffer) {
-        const TileIO io{a, run_off + tile, a.runs[r].msg + tile, threadIdx.x, a.runs[r].sidx,
-                        a.staged ? a.runs[r].soff + tile : run_off + tile};
-        process<MODE, FMT, MT, ALIASED, EMIT>(a, io);
+        const TileIOT<true, ROWS> io{a, run_off + tile, a.runs[r].msg + tile, threadIdx.x, a.runs[r].sidx,
+                                     a.staged ? a.runs[r].soff + tile : run_off + tile};
+        process<MODE, FMT, MT, ALIASED, EMIT, ROWS>(a, io);
     } else if (whole && a.runs[r].path == kPathVector) {
-        const TileIOT<false> io{a, run_off + tile, a.runs[r].msg + tile, threadIdx.x, a.runs[r].sidx,
-                                a.staged ? a.runs[r].soff + tile : run_off + tile};
-        process<MODE, FMT, MT, ALIASED, EMIT>(a, io);
+        const TileIOT<false, ROWS> io{a, run_off + tile, a.runs[r].msg + tile, threadIdx.x, a.runs[r].sidx,
+                                      a.staged ? a.runs[r].soff + tile : run_off + tile};
+        process<MODE, FMT, MT, ALIASED, EMIT, ROWS>(a, io);
     } else {
         const GuardedIO io{a, run_off + tile, tile, a.runs[r].msg + tile, run_n, threadIdx.x, a.runs[r].sidx,
                            a.staged ? a.runs[r].soff + tile : run_off + tile};
-        process<MODE, FMT, 0, ALIASED, EMIT>(a, io);
+        process<MODE, FMT, 0, ALIASED, EMIT, ROWS>(a, io);
     }
 }
 
@@ -780,6 +805,7 @@ void sdl_kernel(const Args a)
 // share a few lines.
 constexpr int kAbsmaxMaxRuns = 64;
 constexpr int kAbsmaxWaves = 4;       // wavefronts per workgroup (50 to 113 VGPRs)
+constexpr int kAbsmaxTile = 512;      // parameters a wavefront takes at a time: 8 per lane
 
 struct AbsmaxRun {
     uint64_t offset;     // first element of the run in the flat arrays
@@ -812,15 +838,15 @@ template <int MB>
 __device__ __forceinline__ void absmax_load(AbsmaxTile<MB>& t, const AbsmaxArgs& a, uint64_t ge, uint64_t we,
                                             uint32_t valid, bool fast, uint32_t lane)
 {
-    if (fast && valid == (uint32_t)kGroup) {
-        const __amdgpu_buffer_rsrc_t rg = rsrc(a.g + ge, kGroup * 4);
+    if (fast && valid == (uint32_t)kAbsmaxTile) {
+        const __amdgpu_buffer_rsrc_t rg = rsrc(a.g + ge, kAbsmaxTile * 4);
         t.g0 = __builtin_amdgcn_raw_buffer_load_b128(rg, (int)(lane * 32), 0, SDL_AUX_LD);
         t.g1 = __builtin_amdgcn_raw_buffer_load_b128(rg, (int)(lane * 32 + 16), 0, SDL_AUX_LD);
 #pragma unroll
         for (int m = 0; m < MB; ++m)
-            t.w[m] = __builtin_amdgcn_raw_buffer_load_b128(rsrc(a.w_send[a.m0 + m] + we, kGroup * 2),
+            t.w[m] = __builtin_amdgcn_raw_buffer_load_b128(rsrc(a.w_send[a.m0 + m] + we, kAbsmaxTile * 2),
                                                            (int)(lane * 16), 0, SDL_AUX_LD);
-    } else if (valid == (uint32_t)kGroup) {
+    } else if (valid == (uint32_t)kAbsmaxTile) {
         // a whole tile of a run that starts at some other element: vectors of element alignment
         const u32x4_f32elem* pg = reinterpret_cast<const u32x4_f32elem*>(a.g + ge + lane * 8);
         t.g0 = __builtin_nontemporal_load(pg);
@@ -866,24 +892,24 @@ __global__ __launch_bounds__(kWave * kAbsmaxWaves) void sdl_span_absmax_kernel(c
     // tiles go to neighbouring workgroups (which the dispatcher deals to different XCDs), not to
     // the wavefronts of one workgroup
     const uint32_t k = wave * run.G + (blockIdx.x - run.first), G = run.G * kAbsmaxWaves;
-    const uint64_t n_tiles = (run.numel + kGroup - 1) / kGroup;
+    const uint64_t n_tiles = (run.numel + kAbsmaxTile - 1) / kAbsmaxTile;
     const bool fast = run.vec != 0u;
     auto valid_of = [&](uint64_t t) -> uint32_t {
-        const uint64_t rem = run.numel - t * kGroup;
-        return rem < (uint64_t)kGroup ? (uint32_t)rem : (uint32_t)kGroup;
+        const uint64_t rem = run.numel - t * kAbsmaxTile;
+        return rem < (uint64_t)kAbsmaxTile ? (uint32_t)rem : (uint32_t)kAbsmaxTile;
     };
-    auto g_elem = [&](uint64_t t) -> uint64_t { return (a.staged ? run.soff : run.offset) + t * kGroup; };
+    auto g_elem = [&](uint64_t t) -> uint64_t { return (a.staged ? run.soff : run.offset) + t * kAbsmaxTile; };
 
     uint32_t amax[MB];
 #pragma unroll
     for (int m = 0; m < MB; ++m) amax[m] = 0u;
 
     AbsmaxTile<MB> cur;
-    if (k < n_tiles) absmax_load<MB>(cur, a, g_elem(k), run.offset + (uint64_t)k * kGroup, valid_of(k), fast, lane);
+    if (k < n_tiles) absmax_load<MB>(cur, a, g_elem(k), run.offset + (uint64_t)k * kAbsmaxTile, valid_of(k), fast, lane);
     for (uint64_t t = k; t < n_tiles; t += G) {
         AbsmaxTile<MB> nxt = cur;
         const uint64_t tn = t + G;
-        if (tn < n_tiles) absmax_load<MB>(nxt, a, g_elem(tn), run.offset + tn * kGroup, valid_of(tn), fast, lane);
+        if (tn < n_tiles) absmax_load<MB>(nxt, a, g_elem(tn), run.offset + tn * kAbsmaxTile, valid_of(tn), fast, lane);
         const uint32_t gb[8] = {cur.g0.x, cur.g0.y, cur.g0.z, cur.g0.w, cur.g1.x, cur.g1.y, cur.g1.z, cur.g1.w};
 #pragma unroll
         for (int m = 0; m < MB; ++m) {
@@ -958,18 +984,19 @@ size_t code_bytes_at(sdl_format_t fmt, uint64_t elem)
 // which is the knob that matters for a streaming kernel: enough loads in flight, not so many
 // that the access window in each array grows and DRAM page locality is lost.  Measured on
 // MI355X (medians of three runs over 302 M parameters, replica counts 2 / 4 / 8): the kernels
-// that write the replicas back want few wavefronts -- fused 8 (12 when w_send aliases w_now),
-// one-pass receive 8 / 12 / 8, merge 16 / 12 / 8 -- while the send side and the receive side
-// without the merge want every wavefront they can get.
+// that write the replicas back want few wavefronts -- fused 12 / 8 / 8 (12 when w_send aliases
+// w_now), one-pass receive 12 / 8 / 8, merge 16 / 12 / 8 --, the receive side without the merge
+// 16 / 16 / all, and the send side every wavefront it can get.
 // SDL_TUNE_LDS_BYTES in the environment overrides the choice (tuning aid).
 uint32_t lds_cap_bytes(int mode, uint32_t mt, bool aliased)
 {
     static const int env = [] { const char* e = std::getenv("SDL_TUNE_LDS_BYTES"); return e ? std::atoi(e) : -1; }();
     if (env >= 0) return (uint32_t)env;
     if (mt == 0) return 0u;
-    if (mode == kFused) return aliased ? 13653u : 20480u;
-    if (mode == kReceive) return mt == 4 ? 13653u : 20480u;
+    if (mode == kFused) return (aliased || mt == 2) ? 13653u : 20480u;
+    if (mode == kReceive) return mt == 2 ? 13653u : 20480u;
     if (mode == kMerge) return mt <= 2 ? 10240u : (mt == 4 ? 13653u : 20480u);
+    if (mode == kReduce) return (mt == 2 || mt == 4) ? 10240u : 0u;
     return 0u;
 }
 
@@ -977,9 +1004,7 @@ template <int MODE, int FMT, bool ALIASED, bool EMIT>
 hipError_t launch_m(const Args& a, uint32_t n_wg, hipStream_t s)
 {
     const dim3 grid(n_wg), block(kWave);
-    // the message-writing fused kernel is a verification aid: one generic-M variant is enough
-    uint32_t mt = (MODE == kFused && EMIT) ? 0u : a.M;
-    if (mt != 1 && mt != 2 && mt != 4 && mt != 8) mt = 0;
+    const uint32_t mt = variant_mt(MODE, a.M, EMIT);   // the grid was sized for this variant's tile
     const uint32_t lds = lds_cap_bytes(MODE, mt, ALIASED);
     switch (mt) {
     case 1: if constexpr (!EMIT) hipLaunchKernelGGL((sdl_kernel<MODE, FMT, 1, ALIASED, EMIT>), grid, block, lds, s, a); break;
@@ -1019,11 +1044,11 @@ hipError_t launch_span_prepass(const Args& a, const SpanRun* runs, uint32_t n_ru
         for (uint32_t m = 0; m < a.M; ++m) { b.w_send[m] = a.w_send[m]; b.scales[m] = a.scales[m]; }
         const uint32_t n = n_runs - r0 < (uint32_t)kAbsmaxMaxRuns ? n_runs - r0 : (uint32_t)kAbsmaxMaxRuns;
         uint64_t total_tiles = 0;
-        for (uint32_t r = 0; r < n; ++r) total_tiles += (runs[r0 + r].numel + kGroup - 1) / kGroup;
+        for (uint32_t r = 0; r < n; ++r) total_tiles += (runs[r0 + r].numel + kAbsmaxTile - 1) / kAbsmaxTile;
         uint32_t next = 0;
         for (uint32_t r = 0; r < n; ++r) {
             const SpanRun& in = runs[r0 + r];
-            const uint64_t tiles = (in.numel + kGroup - 1) / kGroup;
+            const uint64_t tiles = (in.numel + kAbsmaxTile - 1) / kAbsmaxTile;
             uint64_t waves = total_tiles ? (tiles * kAbsmaxGroups + total_tiles - 1) / total_tiles : 1;
             if (waves > tiles) waves = tiles;
             uint64_t G = (waves + kAbsmaxWaves - 1) / kAbsmaxWaves;
@@ -1081,18 +1106,25 @@ struct Align16 {
     Align16 at(bool run_start_aligned) const { return Align16{model && run_start_aligned, msg}; }
 };
 
+// Parameters per workgroup of the kernel variant that a call in this mode will run.
+uint32_t tile_elems(int mode, const Args& a, sdl_format_t fmt)
+{
+    return (uint32_t)(tile_rows(mode, (int)variant_mt(mode, a.M, a.emit != 0u), (int)fmt) * kRow);
+}
+
 // Fill a.runs from a list of (offset, numel); returns the number of workgroups.
 struct RunBuilder {
     Args* a;
+    uint64_t tile;       // parameters per workgroup
     uint64_t n_wg = 0;
-    explicit RunBuilder(Args* args) : a(args) { a->n_runs = 0; }
+    RunBuilder(Args* args, uint32_t tile_elems) : a(args), tile(tile_elems) { a->n_runs = 0; }
     bool full() const { return a->n_runs == kMaxRuns; }
     void add(uint64_t offset, uint64_t numel, TilePath path, uint64_t msg = 0, uint32_t sidx = 0, uint64_t soff = 0)
     {
         Run& r = a->runs[a->n_runs++];
         r.offset = offset; r.numel = numel; r.msg = msg; r.soff = soff; r.first_wg = (uint32_t)n_wg;
         r.path = path; r.sidx = sidx; r.pad_ = 0;
-        n_wg += (numel + kGroup - 1) / kGroup;
+        n_wg += (numel + tile - 1) / tile;
     }
 };
 
@@ -1101,8 +1133,9 @@ template <int MODE>
 int run_single_span(Args& a, uint64_t n, sdl_format_t fmt, Align16 al, void* stream)
 {
     if (n == 0) return SDL_OK;
-    if (n > (uint64_t)0x7fffffff * (uint64_t)kGroup) return SDL_ERR_UNSUPPORTED;
-    RunBuilder rb(&a);
+    const uint32_t tile = tile_elems(MODE, a, fmt);
+    if (n > (uint64_t)0x7fffffff * (uint64_t)tile) return SDL_ERR_UNSUPPORTED;
+    RunBuilder rb(&a, tile);
     rb.add(0, n, al.path());
     if constexpr (MODE == kQuantize || MODE == kFused) {
         if (is_span_scaled(fmt)) {
@@ -1327,14 +1360,14 @@ static int launch_fragment(Args& a, const sdl_plan_t* plan, uint32_t p, Align16 
             if (pieces[i].numel == 0) continue;
             // the run that contains this piece, and where that run starts in the staged arrays
             while (run_i < n_runs && pieces[i].offset >= runs[run_i].offset + runs[run_i].numel) {
-                run_start += (runs[run_i].numel + kGroup - 1) / kGroup * kGroup;
+                run_start += (runs[run_i].numel + kPad - 1) / kPad * kPad;
                 ++run_i;
             }
             const uint64_t soff = run_i < n_runs ? run_start + (pieces[i].offset - runs[run_i].offset) : 0;
             // a piece keeps the 16-byte alignment of the bases when it starts on a multiple of 8 elements
             const Align16 piece_al = al.at((pieces[i].offset % 8 == 0) && (!a.staged || soff % 8 == 0));
             list.push_back(Piece{pieces[i].offset, pieces[i].numel, msg, soff, piece_al, i});
-            msg += (pieces[i].numel + kGroup - 1) / kGroup * kGroup;
+            msg += (pieces[i].numel + kPad - 1) / kPad * kPad;
         }
         if (is_span_scaled(fmt) && (MODE == kQuantize || MODE == kFused)) {
             span_runs.reserve(list.size());
@@ -1349,7 +1382,7 @@ static int launch_fragment(Args& a, const sdl_plan_t* plan, uint32_t p, Align16 
             return SDL_ERR_DEVICE;
     }
     for (size_t first = 0; first < list.size(); first += kMaxRuns) {
-        RunBuilder rb(&a);
+        RunBuilder rb(&a, tile_elems(MODE, a, fmt));
         for (size_t i = first; i < list.size() && i < first + kMaxRuns; ++i)
             rb.add(list[i].offset, list[i].numel, list[i].al.path(), list[i].msg, list[i].sidx, list[i].soff);
         if (rb.n_wg > 0x7fffffffull) return SDL_ERR_UNSUPPORTED;
@@ -1371,7 +1404,7 @@ int sdl_plan_message_bytes(const sdl_plan_t* plan, uint32_t p, sdl_format_t fmt,
                                  : sdl_plan_fragment_runs(plan, p, &runs, &n_runs);
     if (rc != SDL_OK) return rc;
     uint64_t padded = 0;
-    for (uint32_t i = 0; i < n_runs; ++i) padded += (runs[i].numel + kGroup - 1) / kGroup * kGroup;
+    for (uint32_t i = 0; i < n_runs; ++i) padded += (runs[i].numel + kPad - 1) / kPad * kPad;
     sdl_exchange_bytes(fmt, padded, code_bytes, scale_bytes);
     if (is_span_scaled(fmt) && scale_bytes) *scale_bytes = (size_t)n_runs * 4;   // one word per span
     return SDL_OK;
@@ -1537,7 +1570,7 @@ uint64_t sdl_plan_staged_numel(const sdl_plan_t* plan, uint32_t p)
     uint32_t n_runs = 0;
     if (sdl_plan_fragment_runs(plan, p, &runs, &n_runs) != SDL_OK) return 0;
     uint64_t padded = 0;
-    for (uint32_t i = 0; i < n_runs; ++i) padded += (runs[i].numel + kGroup - 1) / kGroup * kGroup;
+    for (uint32_t i = 0; i < n_runs; ++i) padded += (runs[i].numel + kPad - 1) / kPad * kPad;
     return padded;
 }
 int sdl_fragment_outer_step_staged(const sdl_plan_t* plan, uint32_t p, float* g_frag, float* mom_frag,
