@@ -30,11 +30,11 @@ DEFAULT_FRAGMENT = {"tiny": 0, "100m": 1, "1b": 1, "4b_p6": 1, "4b_p1": 0, "stre
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by
 # the reading of the copy kernel); see profiles/.  None = not measured for that workload.
 MEASURED_TRAFFIC_BYTES = {     # (workload, M, format), default fragment of the workload
-    # profiles/fused_e3m0_1b_m4_hbm_traffic.txt: 7.2478e9 B fetched + 4.8323e9 B written per launch
-    ("1b", 4, "e3m0"): 12.0801e9,
+    # profiles/fused_e3m0_1b_m4_hbm_traffic.txt: 7.2480e9 B fetched + 4.8322e9 B written per launch
+    ("1b", 4, "e3m0"): 12.0802e9,
     # profiles/fused_e3m0_other_workloads_hbm_traffic.txt
-    ("stress", 8, "e3m0"): 19.3280e9,
-    ("4b_p6", 2, "e3m0"): 19.0254e9,
+    ("stress", 8, "e3m0"): 19.3283e9,
+    ("4b_p6", 2, "e3m0"): 19.0263e9,
     ("100m", 2, "e3m0"): 0.79297e9,
 }
 

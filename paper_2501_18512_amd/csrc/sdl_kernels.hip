@@ -6,8 +6,8 @@
 // absolute-maximum pre-pass of the whole-span scale is a kernel of its own.
 //
 // Work decomposition (all modes).  A workgroup is one 64-lane wavefront and owns a
-// tile of 512 consecutive parameters, seen as two rows of 256.  Lane l owns the four
-// parameters [4l, 4l+4) of each row, so
+// tile of one or two rows of 256 consecutive parameters (the height is chosen per call and
+// replica count, see tile_rows).  Lane l owns the four parameters [4l, 4l+4) of each row, so
 //   - every memory instruction of the wavefront touches one contiguous piece of an
 //     array (1 KiB of fp32 through 128-bit accesses, 512 B of bf16 through 64-bit
 //     accesses): whole cache lines, nothing strided;
