@@ -1332,7 +1332,7 @@ int sdl_fragment_outer_step(float* g, float* mom, const void* const* w_send, voi
 }  // extern "C"
 
 // One mode over all runs of fragment p, on flat model arrays; the fragment's messages are
-// the concatenation of its runs, each padded to a whole number of 512-element tiles.
+// the concatenation of its runs, each padded to a multiple of 512 elements.
 template <int MODE>
 static int launch_fragment(Args& a, const sdl_plan_t* plan, uint32_t p, Align16 al, sdl_format_t fmt, void* stream)
 {

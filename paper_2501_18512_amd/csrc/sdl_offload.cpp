@@ -12,7 +12,7 @@
 #include "sdl.h"
 
 namespace {
-constexpr uint64_t kTile = 512;    // staged runs are padded to whole kernel tiles
+constexpr uint64_t kTile = 512;    // staged runs are padded to multiples of 512 elements (whole kernel tiles)
 uint64_t pad_tile(uint64_t n) { return (n + kTile - 1) / kTile * kTile; }
 }  // namespace
 
