@@ -52,15 +52,16 @@ enum Mode { kQuantize = 0, kReduce = 1, kMerge = 2, kFused = 3, kReceive = 5 }; 
 // Rows of a workgroup's tile, by call and compile-time replica count (0 = any M at run time).
 // Rows are independent of each other (a scale block never leaves its row), so the height is a
 // pure scheduling choice.  Measured on MI355X over 302 M parameters: one row instead of two gains
-// 1-3 % on the fused kernel and the one-pass receive at M = 2 and 4 and 2-8 % on the receive side
-// without the merge, and loses 2 % on the first two at M = 8, 1-3 % on the merge and 3-7 % on the
-// send side.  The whole-span scale keeps two rows: every tile reads its span's scale words, all
+// 3-5 % on the fused kernel and the one-pass receive at M = 1, 2 and 4, 2-9 % on the receive side
+// without the merge and 7 % on the merge at M = 1, and loses 2 % on the first two at M = 8, 1-3 % on
+// the merge at M >= 2 and 3-12 % on the send side.  The whole-span scale keeps two rows: every tile reads its span's scale words, all
 // tiles of a span the same few bytes, and twice the tiles cost it 8-14 %.
 constexpr int tile_rows(int mode, int mt, int fmt)
 {
     if (fmt == SDL_FMT_E3M0_SPAN) return 2;
-    if (mode == kReduce) return (mt == 2 || mt == 4 || mt == 8) ? 1 : 2;
-    if (mode == kFused || mode == kReceive) return (mt == 2 || mt == 4) ? 1 : 2;
+    if (mode == kReduce) return mt > 0 ? 1 : 2;
+    if (mode == kFused || mode == kReceive) return (mt == 1 || mt == 2 || mt == 4) ? 1 : 2;
+    if (mode == kMerge) return mt == 1 ? 1 : 2;
     return 2;
 }
 // The compile-time replica count a call runs with: the kernels are built for 1, 2, 4 and 8 replicas
@@ -986,16 +987,17 @@ size_t code_bytes_at(sdl_format_t fmt, uint64_t elem)
 // MI355X (medians of three runs over 302 M parameters, replica counts 2 / 4 / 8): the kernels
 // that write the replicas back want few wavefronts -- fused 12 / 8 / 8 (12 when w_send aliases
 // w_now), one-pass receive 12 / 8 / 8, merge 16 / 12 / 8 --, the receive side without the merge
-// 16 / 16 / all, and the send side every wavefront it can get.
+// 16 / 16 / all, and the send side every wavefront it can get.  A single replica: 16 for the fused
+// kernel and the one-pass receive, no cap otherwise.
 // SDL_TUNE_LDS_BYTES in the environment overrides the choice (tuning aid).
 uint32_t lds_cap_bytes(int mode, uint32_t mt, bool aliased)
 {
     static const int env = [] { const char* e = std::getenv("SDL_TUNE_LDS_BYTES"); return e ? std::atoi(e) : -1; }();
     if (env >= 0) return (uint32_t)env;
     if (mt == 0) return 0u;
-    if (mode == kFused) return (aliased || mt == 2) ? 13653u : 20480u;
-    if (mode == kReceive) return mt == 2 ? 13653u : 20480u;
-    if (mode == kMerge) return mt <= 2 ? 10240u : (mt == 4 ? 13653u : 20480u);
+    if (mode == kFused) return mt == 1 ? 10240u : ((aliased || mt == 2) ? 13653u : 20480u);
+    if (mode == kReceive) return mt == 1 ? 10240u : (mt == 2 ? 13653u : 20480u);
+    if (mode == kMerge) return mt == 1 ? 0u : (mt == 2 ? 10240u : (mt == 4 ? 13653u : 20480u));
     if (mode == kReduce) return (mt == 2 || mt == 4) ? 10240u : 0u;
     return 0u;
 }
