@@ -65,7 +65,8 @@ typedef enum {
     SDL_ERR_UNSUPPORTED = -2,
     SDL_ERR_ALIGNMENT = -3,    /* pointer not aligned to its element type */
     SDL_ERR_DEVICE = -4,       /* HIP reported an error at launch */
-    SDL_ERR_NOMEM = -5         /* host allocation failed (plan only) */
+    SDL_ERR_NOMEM = -5,        /* host allocation failed (plan, engine); no free staging slot (offload) */
+    SDL_ERR_TOO_LARGE = -6     /* input exceeds the fixed capacity of an allocation-free entry point */
 } sdl_status_t;
 
 /* Exchange format of the outer gradients (Section 2.4: lower precision for the
@@ -240,6 +241,27 @@ int sdl_fragment_outer_step_plan_ex(const sdl_plan_t* plan, uint32_t p, float* g
                                     const void* const* w_send_base, void* const* w_now_base, uint32_t M,
                                     sdl_format_t fmt, float lr, float mu, float alpha, void* const* codes_or_null,
                                     void* const* scales_or_null, void* stream);
+
+/* sdl_fragment_outer_step_plan for callers that can neither allocate device memory nor hand over
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid allocation.
+ * Same arguments, arithmetic and results as sdl_fragment_outer_step_plan_ex without message output;
+ * unlike sdl_fragment_outer_step_plan it also takes SDL_FMT_E3M0_SPAN, whose scale words (one per
+ * span and replica, the grid-wide maxima of the pre-pass) then live in a device array that is part
+ * of the library image: SDL_STATIC_MAX_SPANS * SDL_MAX_WORKERS 4-byte words (64 KiB) per GPU, held
+ * until the process ends.  The call allocates and frees nothing, on the host or on the device.
+ *   - A fragment with more than SDL_STATIC_MAX_SPANS spans gives SDL_ERR_TOO_LARGE for
+ *     SDL_FMT_E3M0_SPAN (the other formats use no scratch and have no limit); nothing is launched.
+ *   - The array keeps the previous call's contents; every call clears the words it uses with a
+ *     fill kernel (no memset node) before the maxima are taken.
+ *   - All calls on one GPU share the array: two calls with SDL_FMT_E3M0_SPAN that overlap in time
+ *     on the same GPU (different streams, or graphs replayed concurrently) race.  Calls on one
+ *     stream are ordered and safe.
+ *   - The array's device address is looked up at the first call on each device (current device =
+ *     the device of `stream`); make that first call outside graph capture. */
+#define SDL_STATIC_MAX_SPANS 1024
+int sdl_fragment_outer_step_plan_static(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
+                                        const void* const* w_send_base, void* const* w_now_base, uint32_t M,
+                                        sdl_format_t fmt, float lr, float mu, float alpha, void* stream);
 
 /* Fragment-level forms of the send-side and receive-side calls: every run of fragment p
  * of a plan, on the flat model arrays (bases = element 0 of the model).  The messages of a

@@ -90,6 +90,7 @@ def _load() -> ctypes.CDLL:
     lib.sdl_fragment_outer_step_staged.argtypes = lib.sdl_fragment_outer_step_plan.argtypes
     lib.sdl_fragment_outer_step_plan_ex.argtypes = [vp, u32, vp, vp, pp, pp, u32, ctypes.c_int, f32, f32, f32, pp, pp, vp]
     lib.sdl_fragment_outer_step_staged_ex.argtypes = lib.sdl_fragment_outer_step_plan_ex.argtypes
+    lib.sdl_fragment_outer_step_plan_static.argtypes = lib.sdl_fragment_outer_step_plan.argtypes
     lib.sdl_quantize_outer_grad_staged.argtypes = lib.sdl_quantize_outer_grad_plan.argtypes
     lib.sdl_dequant_reduce_nesterov_staged.argtypes = lib.sdl_dequant_reduce_nesterov_plan.argtypes
     lib.sdl_merge_overlap_staged.argtypes = lib.sdl_merge_overlap_plan.argtypes
@@ -322,6 +323,20 @@ def sdl_fragment_outer_step_plan(plan: Plan, p: int, g_base, mom_base, w_send_ba
                                              _ptr_array(w_send_base), _ptr_array(w_now_base),
                                              len(w_send_base), fmt, lr, mu, alpha, _stream(stream)),
            "sdl_fragment_outer_step_plan")
+
+
+STATIC_MAX_SPANS = 1024
+
+
+def sdl_fragment_outer_step_plan_static(plan: Plan, p: int, g_base, mom_base, w_send_base, w_now_base,
+                                        fmt: int, lr: float, mu: float, alpha: float, stream=None):
+    _require_device(g_base, mom_base, *w_send_base, *w_now_base)
+    if len(w_send_base) != len(w_now_base):
+        raise SdlError(-1, "sdl_fragment_outer_step_plan_static")
+    _check(_lib.sdl_fragment_outer_step_plan_static(plan._h, p, _ptr(g_base), _ptr(mom_base),
+                                                    _ptr_array(w_send_base), _ptr_array(w_now_base),
+                                                    len(w_send_base), fmt, lr, mu, alpha, _stream(stream)),
+           "sdl_fragment_outer_step_plan_static")
 
 
 def sdl_fragment_outer_step_plan_ex(plan: Plan, p: int, g_base, mom_base, w_send_base, w_now_base,

@@ -30,11 +30,17 @@
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
-#include <new>
-#include <vector>
+#include <mutex>
 
 #include "sdl.h"
 #include "sdl_device.h"
+
+// Scale words of the allocation-free fused step (sdl_fragment_outer_step_plan_static): for the
+// whole-span scale, one 4-byte word per span and replica, replica m's words at
+// scratch + m * SDL_STATIC_MAX_SPANS.  Every GPU the library runs on holds its own copy of the
+// array at its own address until the process ends.  In host code the name is only a handle for
+// hipGetSymbolAddress: kernels and fills always get the per-device address kept below.
+static __device__ __align__(256) uint32_t scratch[SDL_STATIC_MAX_SPANS * SDL_MAX_WORKERS];
 
 namespace {
 
@@ -1333,32 +1339,24 @@ int sdl_fragment_outer_step(float* g, float* mom, const void* const* w_send, voi
 
 }  // extern "C"
 
-// One mode over all runs of fragment p, on flat model arrays; the fragment's messages are
-// the concatenation of its runs, each padded to a multiple of 512 elements.
-template <int MODE>
-static int launch_fragment(Args& a, const sdl_plan_t* plan, uint32_t p, Align16 al, sdl_format_t fmt, void* stream)
-{
-    // the pieces that are processed: joined runs, or, for the whole-span scale, the spans
-    // themselves (one scale word per parameter group)
-    const sdl_span_t* runs = nullptr;
-    const sdl_span_t* pieces = nullptr;
-    uint32_t n_runs = 0, n_pieces = 0;
-    int rc = sdl_plan_fragment_runs(plan, p, &runs, &n_runs);
-    if (rc != SDL_OK) return rc;
-    if (is_span_scaled(fmt) && MODE != kMerge) rc = sdl_plan_fragment_spans(plan, p, &pieces, &n_pieces);
-    else { pieces = runs; n_pieces = n_runs; }
-    if (rc != SDL_OK) return rc;
-    // where every piece lies: in the flat arrays, in the message arrays (pieces back to back, each
-    // padded to whole tiles), and in staged g / mom (the fragment's runs back to back, each padded
-    // to whole tiles)
+// The pieces of fragment p that one call processes, in model order: the joined runs, or, for the
+// whole-span scale, the spans themselves (one scale word per parameter group).  Yields, for every
+// non-empty piece, where it lies in the flat arrays, in the message arrays (pieces back to back,
+// each padded to whole tiles) and in staged g / mom (the fragment's runs back to back, each padded
+// to whole tiles).  Holds no storage of its own: the callers walk it once per pass.
+struct PieceWalk {
     struct Piece { uint64_t offset, numel, msg, soff; Align16 al; uint32_t sidx; };
-    std::vector<Piece> list;
-    std::vector<SpanRun> span_runs;
-    try {
-        list.reserve(n_pieces);
-        uint64_t msg = 0, run_start = 0;
-        uint32_t run_i = 0;
-        for (uint32_t i = 0; i < n_pieces; ++i) {
+    const sdl_span_t* runs;
+    const sdl_span_t* pieces;
+    uint32_t n_runs, n_pieces;
+    Align16 al;
+    bool staged;
+    uint32_t i = 0, run_i = 0;
+    uint64_t msg = 0, run_start = 0;
+
+    bool next(Piece* out)
+    {
+        for (; i < n_pieces; ++i) {
             if (pieces[i].numel == 0) continue;
             // the run that contains this piece, and where that run starts in the staged arrays
             while (run_i < n_runs && pieces[i].offset >= runs[run_i].offset + runs[run_i].numel) {
@@ -1367,29 +1365,57 @@ static int launch_fragment(Args& a, const sdl_plan_t* plan, uint32_t p, Align16 
             }
             const uint64_t soff = run_i < n_runs ? run_start + (pieces[i].offset - runs[run_i].offset) : 0;
             // a piece keeps the 16-byte alignment of the bases when it starts on a multiple of 8 elements
-            const Align16 piece_al = al.at((pieces[i].offset % 8 == 0) && (!a.staged || soff % 8 == 0));
-            list.push_back(Piece{pieces[i].offset, pieces[i].numel, msg, soff, piece_al, i});
+            const Align16 piece_al = al.at((pieces[i].offset % 8 == 0) && (!staged || soff % 8 == 0));
+            *out = Piece{pieces[i].offset, pieces[i].numel, msg, soff, piece_al, i};
             msg += (pieces[i].numel + kPad - 1) / kPad * kPad;
+            ++i;
+            return true;
         }
-        if (is_span_scaled(fmt) && (MODE == kQuantize || MODE == kFused)) {
-            span_runs.reserve(list.size());
-            for (const Piece& pc : list) span_runs.push_back(SpanRun{pc.offset, pc.numel, pc.soff, pc.al.model, pc.sidx});
-        }
-    } catch (const std::bad_alloc&) {
-        return SDL_ERR_NOMEM;
+        return false;
     }
-    if (!span_runs.empty()) {
+};
+
+// One mode over all runs of fragment p, on flat model arrays; the fragment's messages are
+// the concatenation of its runs, each padded to a multiple of 512 elements.  No host or device
+// memory is allocated on the way.
+template <int MODE>
+static int launch_fragment(Args& a, const sdl_plan_t* plan, uint32_t p, Align16 al, sdl_format_t fmt, void* stream)
+{
+    const sdl_span_t* runs = nullptr;
+    const sdl_span_t* pieces = nullptr;
+    uint32_t n_runs = 0, n_pieces = 0;
+    int rc = sdl_plan_fragment_runs(plan, p, &runs, &n_runs);
+    if (rc != SDL_OK) return rc;
+    if (is_span_scaled(fmt) && MODE != kMerge) rc = sdl_plan_fragment_spans(plan, p, &pieces, &n_pieces);
+    else { pieces = runs; n_pieces = n_runs; }
+    if (rc != SDL_OK) return rc;
+    const PieceWalk start{runs, pieces, n_runs, n_pieces, al, a.staged != 0u};
+    PieceWalk::Piece pc;
+    if (is_span_scaled(fmt) && (MODE == kQuantize || MODE == kFused)) {
         // whole-span scale: clear the scale words, take the grid-wide maxima, then encode
-        if (launch_span_prepass(a, span_runs.data(), (uint32_t)span_runs.size(), (hipStream_t)stream) != hipSuccess)
-            return SDL_ERR_DEVICE;
+        SpanRun batch[kAbsmaxMaxRuns];
+        uint32_t nb = 0;
+        PieceWalk walk = start;
+        for (bool more = walk.next(&pc); more || nb;) {
+            if (more) batch[nb++] = SpanRun{pc.offset, pc.numel, pc.soff, pc.al.model, pc.sidx};
+            more = more && walk.next(&pc);
+            if (nb == (uint32_t)kAbsmaxMaxRuns || !more) {
+                if (launch_span_prepass(a, batch, nb, (hipStream_t)stream) != hipSuccess) return SDL_ERR_DEVICE;
+                nb = 0;
+            }
+        }
     }
-    for (size_t first = 0; first < list.size(); first += kMaxRuns) {
-        RunBuilder rb(&a, tile_elems(MODE, a, fmt));
-        for (size_t i = first; i < list.size() && i < first + kMaxRuns; ++i)
-            rb.add(list[i].offset, list[i].numel, list[i].al.path(), list[i].msg, list[i].sidx, list[i].soff);
-        if (rb.n_wg > 0x7fffffffull) return SDL_ERR_UNSUPPORTED;
-        hipError_t e = launch<MODE>(a, fmt, (uint32_t)rb.n_wg, (hipStream_t)stream);
-        if (e != hipSuccess) return SDL_ERR_DEVICE;
+    const uint32_t tile = tile_elems(MODE, a, fmt);
+    RunBuilder rb(&a, tile);
+    PieceWalk walk = start;
+    for (bool more = walk.next(&pc); more || a.n_runs;) {
+        if (more) rb.add(pc.offset, pc.numel, pc.al.path(), pc.msg, pc.sidx, pc.soff);
+        more = more && walk.next(&pc);
+        if (rb.full() || !more) {
+            if (rb.n_wg > 0x7fffffffull) return SDL_ERR_UNSUPPORTED;
+            if (launch<MODE>(a, fmt, (uint32_t)rb.n_wg, (hipStream_t)stream) != hipSuccess) return SDL_ERR_DEVICE;
+            rb = RunBuilder(&a, tile);
+        }
     }
     return SDL_OK;
 }
@@ -1535,6 +1561,50 @@ int sdl_fragment_outer_step_plan_ex(const sdl_plan_t* plan, uint32_t p, float* g
     return fused_fragment(plan, p, g_base, mom_base, w_send_base, w_now_base, M, fmt, lr, mu, alpha, codes_or_null,
                           scales_or_null, stream, false);
 }
+
+// Device address of `scratch` on the current device, looked up once per device.
+static int static_scratch(uint32_t** out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mutex;
+    static uint32_t* address[kMaxDevices];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SDL_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(mutex);
+    if (!address[dev]) {
+        uint32_t* ptr = nullptr;
+        if (hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SDL_ERR_DEVICE;
+        address[dev] = ptr;
+    }
+    *out = address[dev];
+    return SDL_OK;
+}
+
+int sdl_fragment_outer_step_plan_static(const sdl_plan_t* plan, uint32_t p, float* g_base, float* mom_base,
+                                        const void* const* w_send_base, void* const* w_now_base, uint32_t M,
+                                        sdl_format_t fmt, float lr, float mu, float alpha, void* stream)
+{
+    if (!plan || p >= sdl_plan_num_fragments(plan)) return SDL_ERR_INVALID_ARG;
+    if (!valid_format(fmt) || M == 0 || M > SDL_MAX_WORKERS) return SDL_ERR_INVALID_ARG;
+    if (!is_span_scaled(fmt))   // no other format needs memory beyond the model arrays
+        return fused_fragment(plan, p, g_base, mom_base, w_send_base, w_now_base, M, fmt, lr, mu, alpha, nullptr,
+                              nullptr, stream, false);
+    const sdl_span_t* spans = nullptr;
+    uint32_t n_spans = 0;
+    int rc = sdl_plan_fragment_spans(plan, p, &spans, &n_spans);
+    if (rc != SDL_OK) return rc;
+    if (n_spans > SDL_STATIC_MAX_SPANS) return SDL_ERR_TOO_LARGE;
+    uint32_t* base = nullptr;
+    rc = static_scratch(&base);
+    if (rc != SDL_OK) return rc;
+    void* words[SDL_MAX_WORKERS];
+    for (uint32_t m = 0; m < M; ++m) words[m] = base + (size_t)m * SDL_STATIC_MAX_SPANS;
+    // the pre-pass clears the words of the fragment's spans with a fill kernel before it takes the
+    // maxima, so what an earlier call left in the array does not matter
+    return fused_fragment(plan, p, g_base, mom_base, w_send_base, w_now_base, M, fmt, lr, mu, alpha, nullptr, words,
+                          stream, false);
+}
+
 int sdl_quantize_outer_grad_plan(const sdl_plan_t* plan, uint32_t p, const float* g_base,
                                  const void* const* w_send_base, uint32_t M, sdl_format_t fmt,
                                  void* const* codes, void* const* scales, void* stream)

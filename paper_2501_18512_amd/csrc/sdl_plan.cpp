@@ -195,7 +195,8 @@ const char* sdl_status_string(int status)
     case SDL_ERR_UNSUPPORTED: return "unsupported";
     case SDL_ERR_ALIGNMENT: return "pointer not aligned to its element type";
     case SDL_ERR_DEVICE: return "HIP error at kernel launch";
-    case SDL_ERR_NOMEM: return "out of host memory";
+    case SDL_ERR_NOMEM: return "out of host memory or staging slots";
+    case SDL_ERR_TOO_LARGE: return "input exceeds the fixed capacity of the allocation-free entry point";
     default: return "unknown status";
     }
 }
