@@ -175,7 +175,7 @@ size_t sdl_exchange_bytes(sdl_format_t fmt, uint64_t numel, size_t* code_bytes, 
 
 /* ------------------------------------------------------------------ device calls */
 
-/* Send side (Algorithm 2, "if t - t_p mod H == 0" branch; Section 2.4): for every
+/* Send side (Algorithm 2, the first conditional: the step at which fragment p is due; Section 2.4): for every
  * replica m, delta_m[i] = g[i] - float(w_send[m][i]) (one fp32 subtraction), encoded
  * in fmt into codes[m] (and scales[m] for E4M3 / E3M0).
  *   g        device, fp32[n], read
@@ -186,8 +186,9 @@ size_t sdl_exchange_bytes(sdl_format_t fmt, uint64_t numel, size_t* code_bytes, 
 int sdl_quantize_outer_grad(const float* g, const void* const* w_send, uint32_t M, uint64_t n,
                             sdl_format_t fmt, void* const* codes, void* const* scales, void* stream);
 
-/* Receive side (Algorithm 2, "if t - t_p - tau mod H == 0" branch; Section 2.4: the
- * accumulation is done in FP32; Section 2.1: OuterOpt is SGD with Nesterov momentum):
+/* Receive side (Algorithm 2, the second conditional: tau steps after the send; Section 2.4:
+ * FP32 accumulation of the received outer gradients; Section 2.1: OuterOpt is SGD with Nesterov
+ * momentum):
  *   d[i]   = (sum over m = 0..M-1, in that order, starting from +0, of decode_m[i]) / M
  *   mom[i] = mu * mom[i] + d[i]
  *   g[i]   = g[i] - lr * (d[i] + mu * mom[i])          (new mom)
@@ -204,7 +205,8 @@ int sdl_dequant_reduce_nesterov(float* g, float* mom, const void* const* codes,
 int sdl_merge_overlap(const float* g_new, void* const* w_now, uint32_t M, uint64_t n, float alpha,
                       void* stream);
 
-/* Receive side in one pass: sdl_dequant_reduce_nesterov followed by sdl_merge_overlap of all
+/* Receive side in one pass (Algorithm 2, everything under the second conditional: receive, OuterOpt
+ * and the mixing statement; Section 2.3): sdl_dequant_reduce_nesterov followed by sdl_merge_overlap of all
  * M replicas, without re-reading the new global parameters (16 + 4M + M*c bytes per parameter
  * instead of 20 + 4M + M*c).  Use it when every worker merges at the step the mean is taken
  * (one common delay tau); results are identical to the two separate calls. */
@@ -263,7 +265,8 @@ int sdl_fragment_outer_step_plan_static(const sdl_plan_t* plan, uint32_t p, floa
                                         const void* const* w_send_base, void* const* w_now_base, uint32_t M,
                                         sdl_format_t fmt, float lr, float mu, float alpha, void* stream);
 
-/* Fragment-level forms of the send-side and receive-side calls: every run of fragment p
+/* Fragment-level forms of the send-side and receive-side calls (Section 2.2: what is synchronised at a
+ * step is a fragment, a subset of the transformer blocks, not the whole model): every run of fragment p
  * of a plan, on the flat model arrays (bases = element 0 of the model).  The messages of a
  * fragment are laid out as the concatenation of its runs, each run padded to a multiple
  * of 512 elements; sdl_plan_message_bytes gives the size of codes[m] / scales[m] for that
@@ -299,7 +302,10 @@ int sdl_receive_outer_step_plan(const sdl_plan_t* plan, uint32_t p, float* g_bas
  * different steps); the mean and the Nesterov update happen once, at the smallest delay,
  * and each worker merges when its own delay expires.
  * The plan must outlive the engine.  H must be the H the plan was built with.  Steps must
- * be fed in order without gaps (a skipped receive is reported as SDL_ERR_INVALID_ARG).
+ * be fed in order without gaps: a step that finds a send, receive or merge of an earlier step
+ * undone is refused with SDL_ERR_INVALID_ARG before anything is launched.  SDL_ERR_DEVICE (a launch
+ * or copy failed) can come after earlier fragments of the same step were launched; the engine's
+ * state is then undefined and it must be destroyed.
  * sdl_engine_bind: g_base, mom_base, w_base[M] = flat device arrays (the live replicas);
  * codes / scales = host arrays of P*M device pointers, entry p*M + m sized by
  * sdl_plan_message_bytes(plan, p, ...); both may be NULL when every delay is 0 (except that
@@ -348,7 +354,10 @@ int sdl_receive_outer_step_staged(const sdl_plan_t* plan, uint32_t p, float* g_f
  * memory is the caller's.
  *   prefetch  starts the host-to-device copy of fragment p into a free slot on copy_stream
  *             (SDL_ERR_NOMEM if every slot is taken; no-op if p is already staged)
- *   acquire   prefetch if needed, make compute_stream wait for the copy, return the slot
+ *   acquire   make compute_stream wait for the copy and return the slot; a fragment that is not staged
+ *             yet is copied into a free slot, else into the slot of a fragment that was prefetched but
+ *             never acquired (that copy is dropped: it holds nothing the host arrays do not);
+ *             SDL_ERR_NOMEM only if every slot is held by an acquired fragment
  *   release   after the work queued on compute_stream: copy the fragment back to the host
  *             arrays on copy_stream and free the slot
  *   flush     write every staged fragment back without freeing its slot (checkpointing)
@@ -356,11 +365,15 @@ int sdl_receive_outer_step_staged(const sdl_plan_t* plan, uint32_t p, float* g_f
  * copy-in of a slot are ordered by it).  Host arrays are valid after the copy stream has
  * been synchronised.  sdl_engine_bind_offload makes an engine take g / mom from the pool
  * instead of flat device arrays; it prefetches the fragments that send within `lookahead`
- * steps. */
+ * steps, in the order of their send steps.  The pool needs one slot for every fragment that can be
+ * between its send step and its last merge at the same time (offsets, H and the largest delay decide;
+ * one slot when no worker has a delay); fewer give SDL_ERR_INVALID_ARG here, so that a step never
+ * runs out of slots half way. */
 typedef struct sdl_offload sdl_offload_t;
 int sdl_offload_create(const sdl_plan_t* plan, uint32_t n_slots, sdl_offload_t** out);
 void sdl_offload_destroy(sdl_offload_t* pool);
 uint64_t sdl_offload_slot_numel(const sdl_offload_t* pool);
+uint32_t sdl_offload_num_slots(const sdl_offload_t* pool);
 int sdl_offload_bind(sdl_offload_t* pool, float* g_host, float* mom_host, float* const* slot_g,
                      float* const* slot_mom);
 int sdl_offload_resident(const sdl_offload_t* pool, uint32_t p);
@@ -443,9 +456,17 @@ typedef enum { SDL_EVAL_FIRST_REPLICA = 0, SDL_EVAL_REPLICA_MEAN = 1, SDL_EVAL_O
 int sdl_evaluation_params(sdl_eval_params_t which, const float* g, const void* const* w, uint32_t M, uint64_t numel,
                           void* out_bf16, void* stream);
 
-/* Plain device-to-device streaming copy of nbytes (a multiple of 16; both pointers
- * 16-byte aligned).  Not part of the method: it is the yardstick against which the
- * achieved memory bandwidth of the calls above is judged (2 * nbytes of traffic). */
+/* Memory-system yardsticks.  Not part of the method: they are what the achieved bandwidth of the
+ * calls above is judged against.  nbytes is a multiple of 16, both pointers are 16-byte aligned.
+ *   SDL_PROBE_COPY      plain device-to-device copy (2 * nbytes of traffic); also the kernel of known
+ *                       size that the profiler's HBM counters are calibrated with
+ *   SDL_PROBE_COPY_NT   the same copy with the non-temporal policy the method's kernels use
+ *   SDL_PROBE_READ_NT   reads src and writes nothing (nbytes of traffic); dst must still point at 16
+ *                       valid bytes (written only if the data spell one particular value)
+ *   SDL_PROBE_FILL_NT   writes dst and reads nothing (nbytes of traffic); src is ignored
+ * sdl_copy_bytes(dst, src, n, s) is sdl_memory_probe(SDL_PROBE_COPY, dst, src, n, s). */
+typedef enum { SDL_PROBE_COPY = 0, SDL_PROBE_COPY_NT = 1, SDL_PROBE_READ_NT = 2, SDL_PROBE_FILL_NT = 3 } sdl_probe_t;
+int sdl_memory_probe(sdl_probe_t kind, void* dst, const void* src, uint64_t nbytes, void* stream);
 int sdl_copy_bytes(void* dst, const void* src, uint64_t nbytes, void* stream);
 
 const char* sdl_status_string(int status);

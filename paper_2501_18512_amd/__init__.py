@@ -99,6 +99,8 @@ def _load() -> ctypes.CDLL:
     lib.sdl_offload_destroy.restype = None
     lib.sdl_offload_slot_numel.argtypes = [vp]
     lib.sdl_offload_slot_numel.restype = u64
+    lib.sdl_offload_num_slots.argtypes = [vp]
+    lib.sdl_offload_num_slots.restype = u32
     lib.sdl_offload_bind.argtypes = [vp, vp, vp, pp, pp]
     lib.sdl_offload_resident.argtypes = [vp, u32]
     lib.sdl_offload_prefetch.argtypes = [vp, u32, vp]
@@ -107,6 +109,7 @@ def _load() -> ctypes.CDLL:
     lib.sdl_offload_flush.argtypes = [vp, vp, vp]
     lib.sdl_engine_bind_offload.argtypes = [vp, vp, pp, pp, pp, vp, u32]
     lib.sdl_copy_bytes.argtypes = [vp, vp, u64, vp]
+    lib.sdl_memory_probe.argtypes = [ctypes.c_int, vp, vp, u64, vp]
     lib.sdl_engine_track_cosine.argtypes = [vp, pp, vp, vp, ctypes.c_size_t]
     lib.sdl_evaluation_params.argtypes = [ctypes.c_int, vp, pp, u32, u64, vp, vp]
     lib.sdl_cosine_workspace_bytes.argtypes = [u32, u32]
@@ -513,6 +516,14 @@ def sdl_engine_bind_offload(engine: Engine, pool: Offload, w_base, codes=None, s
                                         _ptr_array(scales), _stream(copy_stream), lookahead),
            "sdl_engine_bind_offload")
     engine._keep = (pool, list(w_base), codes, scales, copy_stream)
+
+
+PROBE_COPY, PROBE_COPY_NT, PROBE_READ_NT, PROBE_FILL_NT = 0, 1, 2, 3
+
+
+def sdl_memory_probe(kind: int, dst, src, nbytes: int, stream=None):
+    _require_device(dst, src)
+    _check(_lib.sdl_memory_probe(kind, _ptr(dst), _ptr(src), nbytes, _stream(stream)), "sdl_memory_probe")
 
 
 def sdl_copy_bytes(dst, src, nbytes: int, stream=None):

@@ -25,7 +25,6 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
-#include <cstdlib>
 
 #include "sdl.h"
 #include "sdl_device.h"
@@ -43,9 +42,6 @@ constexpr int kMaxPieces = kMaxSets + kWindows;
 constexpr uint32_t kGroups = 8192;              // workgroups per launch, shared out among the sets (32 per compute unit)
 constexpr uint32_t kMaxGroups = 8192;           // what the workspace is sized for
 
-#ifndef SDL_GRAM_PREFETCH
-#define SDL_GRAM_PREFETCH 1      // issue the next tile's loads before the current tile is consumed
-#endif
 
 struct Set {
     uint64_t offset;     // first element in the flat arrays
@@ -195,8 +191,8 @@ __global__ void __launch_bounds__(kWave) sdl_gram_kernel(const GramArgs a)
         }
     };
 
-#if SDL_GRAM_PREFETCH
-    // workgroup k's tiles: first, first + step, ... below end
+    // workgroup k's tiles: first, first + step, ... below end; the next tile's loads are issued before the
+    // current tile is consumed
     const uint64_t first = k, step = set.G, end = n_tiles;
     TileRegs<NW> cur;
     if (first < end) load_tile<NW>(cur, a.g, w, set.offset + first * kTile, valid_of(first), fast, lane);
@@ -207,13 +203,6 @@ __global__ void __launch_bounds__(kWave) sdl_gram_kernel(const GramArgs a)
         consume(cur);
         cur = nxt;
     }
-#else
-    for (uint64_t t = k; t < n_tiles; t += set.G) {
-        TileRegs<NW> cur;
-        load_tile<NW>(cur, a.g, w, set.offset + t * kTile, valid_of(t), fast, lane);
-        consume(cur);
-    }
-#endif
 
     double* out = a.partial + (uint64_t)blockIdx.x * a.M * a.M;
 #pragma unroll
@@ -284,25 +273,8 @@ __global__ void __launch_bounds__(256) sdl_gram_finalize(const FinArgs f)
 
 // ------------------------------------------------------------------ host side
 
-uint32_t windows_per_launch()
-{
-    // tuning knob for sweeps; the default is what ships
-    if (const char* e = std::getenv("SDL_TUNE_GRAM_WINDOWS")) {
-        const long v = std::strtol(e, nullptr, 10);
-        if (v >= 1 && v <= (long)kWindows) return (uint32_t)v;
-    }
-    return kWindows;
-}
-
-uint32_t groups_per_launch()
-{
-    // tuning knob for sweeps; the default is what ships
-    if (const char* e = std::getenv("SDL_TUNE_GRAM_GROUPS")) {
-        const long v = std::strtol(e, nullptr, 10);
-        if (v >= 1 && v <= (long)kMaxGroups) return (uint32_t)v;
-    }
-    return kGroups;
-}
+uint32_t windows_per_launch() { return kWindows; }
+uint32_t groups_per_launch() { return kGroups; }
 
 template <int MR, bool DIAG>
 int launch_block_c(int mc, const GramArgs& a, hipStream_t st)

@@ -3,7 +3,9 @@
 // staggered fragments; Section 2.3: the result of a send is consumed tau steps later, with
 // an optional different delay per worker, Section 3.3.2 "slack between workers").
 // Uses only the plan-level entry points of sdl.h; no device code here.
+#include <algorithm>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "sdl.h"
@@ -30,6 +32,7 @@ struct sdl_engine {
     std::vector<uint64_t> sent_at;
     std::vector<uint8_t> reduced;
     std::vector<uint8_t> merged;         // P*M
+    std::vector<std::pair<uint64_t, uint32_t>> due;   // (next send step, fragment) of the prefetch candidates
     // optional diagnostics: cosine similarity of the outer gradients at every send
     bool track_cosine = false;
     std::vector<double*> cos_span_results;   // per fragment, may hold null pointers
@@ -69,6 +72,7 @@ int sdl_engine_create(const sdl_plan_t* plan, uint32_t H, uint32_t M, const uint
         e->sent_at.assign(e->P, 0);
         e->reduced.assign(e->P, 0);
         e->merged.assign((size_t)e->P * M, 0);
+        e->due.reserve(e->P);
     } catch (const std::bad_alloc&) {
         delete e;
         return SDL_ERR_NOMEM;
@@ -101,6 +105,20 @@ static int bind_replicas_and_messages(sdl_engine* e, void* const* w_base, void* 
     return SDL_OK;
 }
 
+// Largest number of fragments that are between their send step and their last merge at the same
+// inner step (at least 1: a fragment that is synchronised within one step still needs a slot).
+static uint32_t slots_needed(const sdl_engine* e)
+{
+    uint32_t most = 1;
+    for (uint32_t phase = 0; phase < e->H; ++phase) {
+        uint32_t n = 0;
+        for (uint32_t p = 0; p < e->P; ++p)
+            if ((phase + e->H - e->offset[p]) % e->H <= e->delay_max) ++n;
+        if (n > most) most = n;
+    }
+    return most;
+}
+
 int sdl_engine_bind(sdl_engine_t* e, float* g_base, float* mom_base, void* const* w_base, void* const* codes,
                     void* const* scales)
 {
@@ -117,6 +135,9 @@ int sdl_engine_bind_offload(sdl_engine_t* e, sdl_offload_t* offload, void* const
                             void* const* scales, void* copy_stream, uint32_t lookahead)
 {
     if (!e || !offload) return SDL_ERR_INVALID_ARG;
+    // a fragment holds its slot from its send step until its last worker has merged (delay_max steps
+    // later): the pool must have a slot for every fragment that can be in that state at once
+    if (sdl_offload_num_slots(offload) < slots_needed(e)) return SDL_ERR_INVALID_ARG;
     int rc = bind_replicas_and_messages(e, w_base, codes, scales);
     if (rc != SDL_OK) return rc;
     e->g = e->mom = nullptr;          // the outer state is reached through the staging pool only
@@ -165,6 +186,19 @@ int sdl_engine_step(sdl_engine_t* e, uint64_t t, void* stream, uint32_t* n_sent,
     uint32_t sent = 0, received = 0;
     const uint32_t M = e->M;
     const bool staged = e->offload != nullptr;
+    // everything that depends on the engine's own state is checked before the first launch, so that a
+    // step that is refused has done nothing
+    for (uint32_t p = 0; p < e->P; ++p) {
+        const uint64_t s0 = e->offset[p];
+        const bool sends = t > s0 && (t - s0) % e->H == 0;
+        if (sends && e->sent_at[p] != 0) return SDL_ERR_INVALID_ARG;         // previous message not consumed: steps skipped
+        if (sends && e->track_cosine && staged) return SDL_ERR_UNSUPPORTED;
+        if (e->sent_at[p] != 0) {
+            const uint64_t ts = e->sent_at[p];
+            if (!e->reduced[p] && t > ts + e->delay_min) return SDL_ERR_INVALID_ARG;   // the receive step was skipped
+            if (t > ts + e->delay_max) return SDL_ERR_INVALID_ARG;                   // a merge step was skipped
+        }
+    }
     for (uint32_t p = 0; p < e->P; ++p) {
         void* const* codes = e->codes.data() + (size_t)p * M;
         void* const* scales = e->scales.data() + (size_t)p * M;
@@ -180,10 +214,8 @@ int sdl_engine_step(sdl_engine_t* e, uint64_t t, void* stream, uint32_t* n_sent,
             if (rc != SDL_OK) return rc;
         }
         if (sends) {
-            if (e->sent_at[p] != 0) return SDL_ERR_INVALID_ARG;      // previous message not consumed: steps skipped
             if (e->track_cosine) {
                 // the outer gradients that are about to be sent, before anything is updated
-                if (staged) return SDL_ERR_UNSUPPORTED;
                 int rc = sdl_outer_grad_cosine_plan(e->plan, p, g, e->w.data(), M, e->cos_span_results[p],
                                                     e->cos_fragment_results + (size_t)p * SDL_COSINE_RESULT_DOUBLES(M),
                                                     e->cos_workspace, e->cos_workspace_bytes, stream);
@@ -245,7 +277,6 @@ int sdl_engine_step(sdl_engine_t* e, uint64_t t, void* stream, uint32_t* n_sent,
                 n_done += done;
             }
             if (n_due) {
-                if (!e->reduced[p]) return SDL_ERR_INVALID_ARG;
                 int rc = staged ? sdl_merge_overlap_staged(e->plan, p, g, due, n_due, e->alpha, stream)
                                 : sdl_merge_overlap_plan(e->plan, p, g, due, n_due, e->alpha, stream);
                 if (rc != SDL_OK) return rc;
@@ -257,22 +288,27 @@ int sdl_engine_step(sdl_engine_t* e, uint64_t t, void* stream, uint32_t* n_sent,
                     int rc = sdl_offload_release(e->offload, p, stream, e->copy_stream);
                     if (rc != SDL_OK) return rc;
                 }
-            } else if (t > ts + e->delay_max) {
-                return SDL_ERR_INVALID_ARG;   // steps were skipped
             }
         }
     }
-    if (staged) {
-        // the schedule is known in advance: start copying in the fragments that send within the
-        // next `lookahead` steps (a full pool of slots just means they are fetched on demand)
-        for (uint32_t p = 0; p < e->P && e->lookahead > 0; ++p) {
+    if (staged && e->lookahead > 0) {
+        // the schedule is known in advance: start copying in the fragments that send within the next
+        // `lookahead` steps, the one that is due first first.  A full pool ends the round: a fragment
+        // that could not be prefetched is copied in when it is due, where a copy that was prefetched
+        // too early and not used yet gives way to it.
+        e->due.clear();                           // capacity P since creation: no allocation here
+        for (uint32_t p = 0; p < e->P; ++p) {
+            if (e->sent_at[p] != 0) continue;
             const uint64_t s0 = e->offset[p];
             const uint64_t k = t >= s0 ? (t - s0) / e->H + 1 : 1;     // next send strictly after t
             const uint64_t next = s0 + k * e->H;
-            if (next - t <= e->lookahead && e->sent_at[p] == 0) {
-                int rc = sdl_offload_prefetch(e->offload, p, e->copy_stream);
-                if (rc != SDL_OK && rc != SDL_ERR_NOMEM) return rc;
-            }
+            if (next - t <= e->lookahead) e->due.push_back(std::make_pair(next, p));
+        }
+        std::sort(e->due.begin(), e->due.end());
+        for (const auto& d : e->due) {
+            const int rc = sdl_offload_prefetch(e->offload, d.second, e->copy_stream);
+            if (rc == SDL_ERR_NOMEM) break;
+            if (rc != SDL_OK) return rc;
         }
     }
     if (n_sent) *n_sent = sent;

@@ -28,7 +28,6 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
-#include <cstdlib>
 #include <cstring>
 #include <mutex>
 
@@ -123,19 +122,10 @@ struct Args {
 };
 
 // Cache policy bits of the buffer instructions on gfx950: 1 = sc0, 2 = nt, 16 = sc1.
-#ifndef SDL_AUX_LD
-#define SDL_AUX_LD 2         // loads: non-temporal
-#endif
-#ifndef SDL_AUX_ST
-#define SDL_AUX_ST 2         // stores: non-temporal
-#endif
-#ifndef SDL_AUX_SCALE
-#define SDL_AUX_SCALE 0      // scale bytes: 16 per tile, 8 tiles per cache line -> let L2 combine them
-#endif
-
-#ifndef SDL_WAVES_PER_EU
-#define SDL_WAVES_PER_EU 2   // register budget: at least this many wavefronts per SIMD
-#endif
+constexpr int kAuxLoad = 2;      // loads: non-temporal (every byte is touched once)
+constexpr int kAuxStore = 2;     // stores: non-temporal
+constexpr int kAuxScale = 0;     // scale bytes: 16 per tile, 8 tiles per cache line -> let L2 combine them
+constexpr int kWavesPerEu = 2;   // register budget: at least this many wavefronts per SIMD
 
 // ------------------------------------------------------------------ bit helpers
 
@@ -360,7 +350,7 @@ struct TileIOT {
         } else {
             constexpr int B = block_elems(FMT);
             const uint32_t sb = __builtin_amdgcn_raw_buffer_load_b8(
-                rsrc(a.scales[m] + tb / B, kTile / B), (int)(row * (kRow / B) + lane / (B / kVec)), 0, SDL_AUX_SCALE);
+                rsrc(a.scales[m] + tb / B, kTile / B), (int)(row * (kRow / B) + lane / (B / kVec)), 0, kAuxScale);
             return scale_from_byte(sb);
         }
     }
@@ -370,33 +360,33 @@ struct TileIOT {
             constexpr int B = block_elems(FMT);
             if ((lane % (B / kVec)) == 0u)
                 __builtin_amdgcn_raw_buffer_store_b8((uint8_t)sb, rsrc(a.scales[m] + tb / B, kTile / B),
-                                                     (int)(row * (kRow / B) + lane / (B / kVec)), 0, SDL_AUX_SCALE);
+                                                     (int)(row * (kRow / B) + lane / (B / kVec)), 0, kAuxScale);
         }
     }
     // p = address of the tile's first element in the array
     __device__ __forceinline__ void ld_f32(const float* p, int row, float (&v)[kVec]) const
     {
         const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rsrc(p, kTile * 4),
-                                                              (int)(row * kRow * 4 + lane * 16), 0, SDL_AUX_LD);
+                                                              (int)(row * kRow * 4 + lane * 16), 0, kAuxLoad);
         v[0] = u2f(x.x); v[1] = u2f(x.y); v[2] = u2f(x.z); v[3] = u2f(x.w);
     }
     __device__ __forceinline__ void st_f32(float* p, int row, const float (&v)[kVec]) const
     {
         const u32x4 x = {f2u(v[0]), f2u(v[1]), f2u(v[2]), f2u(v[3])};
         __builtin_amdgcn_raw_buffer_store_b128(x, rsrc(p, kTile * 4), (int)(row * kRow * 4 + lane * 16), 0,
-                                               SDL_AUX_ST);
+                                               kAuxStore);
     }
     __device__ __forceinline__ void ld_bf16(const uint16_t* p, int row, uint32_t (&u)[2]) const
     {
         const u32x2 x = __builtin_amdgcn_raw_buffer_load_b64(rsrc(p, kTile * 2),
-                                                             (int)(row * kRow * 2 + lane * 8), 0, SDL_AUX_LD);
+                                                             (int)(row * kRow * 2 + lane * 8), 0, kAuxLoad);
         u[0] = x.x; u[1] = x.y;
     }
     __device__ __forceinline__ void st_bf16(uint16_t* p, int row, const uint32_t (&u)[2]) const
     {
         const u32x2 x = {u[0], u[1]};
         __builtin_amdgcn_raw_buffer_store_b64(x, rsrc(p, kTile * 2), (int)(row * kRow * 2 + lane * 8), 0,
-                                              SDL_AUX_ST);
+                                              kAuxStore);
     }
 
     // the model arrays: the buffer path above when the tile is 16-byte aligned in all of them,
@@ -464,11 +454,11 @@ struct TileIOT {
             if constexpr (is_e3m0(FMT)) {
                 const uint32_t c0 = __builtin_amdgcn_raw_buffer_load_b16(rsrc(codes + tb / 2, kTile / 2),
                                                                          (int)(row * (kRow / 2) + lane * 2), 0,
-                                                                         SDL_AUX_LD);
+                                                                         kAuxLoad);
                 decode_e3m0(c0, scale, dq);
             } else {
                 const uint32_t c0 = __builtin_amdgcn_raw_buffer_load_b32(rsrc(codes + tb, kTile),
-                                                                         (int)(row * kRow + lane * 4), 0, SDL_AUX_LD);
+                                                                         (int)(row * kRow + lane * 4), 0, kAuxLoad);
                 decode_e4m3<EXACT>(c0, scale, dq);
             }
         }
@@ -480,19 +470,19 @@ struct TileIOT {
         if constexpr (FMT == SDL_FMT_FP32) {
             const u32x4 x = {c[0], c[1], c[2], c[3]};
             __builtin_amdgcn_raw_buffer_store_b128(x, rsrc(codes + tb * 4, kTile * 4),
-                                                   (int)(row * kRow * 4 + lane * 16), 0, SDL_AUX_ST);
+                                                   (int)(row * kRow * 4 + lane * 16), 0, kAuxStore);
         } else if constexpr (FMT == SDL_FMT_BF16) {
             const u32x2 x = {c[0], c[1]};
             __builtin_amdgcn_raw_buffer_store_b64(x, rsrc(codes + tb * 2, kTile * 2),
-                                                  (int)(row * kRow * 2 + lane * 8), 0, SDL_AUX_ST);
+                                                  (int)(row * kRow * 2 + lane * 8), 0, kAuxStore);
         } else {
             store_scale<FMT>(m, row, sb);
             if constexpr (is_e3m0(FMT)) {
                 __builtin_amdgcn_raw_buffer_store_b16((uint16_t)c[0], rsrc(codes + tb / 2, kTile / 2),
-                                                      (int)(row * (kRow / 2) + lane * 2), 0, SDL_AUX_ST);
+                                                      (int)(row * (kRow / 2) + lane * 2), 0, kAuxStore);
             } else {
                 __builtin_amdgcn_raw_buffer_store_b32(c[0], rsrc(codes + tb, kTile), (int)(row * kRow + lane * 4), 0,
-                                                      SDL_AUX_ST);
+                                                      kAuxStore);
             }
         }
     }
@@ -771,7 +761,7 @@ __device__ __forceinline__ void process(const Args& a, const IO& io)
 // ------------------------------------------------------------------ the kernel
 
 template <int MODE, int FMT, int MT, bool ALIASED, bool EMIT>
-__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(SDL_WAVES_PER_EU)))
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(kWavesPerEu)))
 void sdl_kernel(const Args a)
 {
     // which run does this workgroup work on (uniform scan of at most kMaxRuns entries)
@@ -847,12 +837,12 @@ __device__ __forceinline__ void absmax_load(AbsmaxTile<MB>& t, const AbsmaxArgs&
 {
     if (fast && valid == (uint32_t)kAbsmaxTile) {
         const __amdgpu_buffer_rsrc_t rg = rsrc(a.g + ge, kAbsmaxTile * 4);
-        t.g0 = __builtin_amdgcn_raw_buffer_load_b128(rg, (int)(lane * 32), 0, SDL_AUX_LD);
-        t.g1 = __builtin_amdgcn_raw_buffer_load_b128(rg, (int)(lane * 32 + 16), 0, SDL_AUX_LD);
+        t.g0 = __builtin_amdgcn_raw_buffer_load_b128(rg, (int)(lane * 32), 0, kAuxLoad);
+        t.g1 = __builtin_amdgcn_raw_buffer_load_b128(rg, (int)(lane * 32 + 16), 0, kAuxLoad);
 #pragma unroll
         for (int m = 0; m < MB; ++m)
             t.w[m] = __builtin_amdgcn_raw_buffer_load_b128(rsrc(a.w_send[a.m0 + m] + we, kAbsmaxTile * 2),
-                                                           (int)(lane * 16), 0, SDL_AUX_LD);
+                                                           (int)(lane * 16), 0, kAuxLoad);
     } else if (valid == (uint32_t)kAbsmaxTile) {
         // a whole tile of a run that starts at some other element: vectors of element alignment
         const u32x4_f32elem* pg = reinterpret_cast<const u32x4_f32elem*>(a.g + ge + lane * 8);
@@ -957,13 +947,32 @@ __global__ __launch_bounds__(SDL_MAX_WORKERS * kAbsmaxMaxRuns) void sdl_zero_spa
     if (m < a.M && r < a.n_runs) reinterpret_cast<uint32_t*>(a.scales[m])[a.runs[r].sidx] = 0u;
 }
 
-// Plain streaming copy, 16 bytes per lane: the yardstick for the HBM roofline.
+// Streaming yardsticks for the HBM roofline, 16 bytes per lane: a plain copy, and the same copy, a
+// read-only pass and a write-only pass with the non-temporal policy the method's kernels use.
 constexpr int kCopyThreads = 256;
 __global__ __launch_bounds__(kCopyThreads) void sdl_copy_kernel(uint4* __restrict__ dst,
                                                             const uint4* __restrict__ src, uint64_t n16)
 {
     const uint64_t i = (uint64_t)blockIdx.x * kCopyThreads + threadIdx.x;
     if (i < n16) dst[i] = src[i];
+}
+template <int KIND>
+__global__ __launch_bounds__(kCopyThreads) void sdl_probe_kernel(u32x4* __restrict__ dst,
+                                                             const u32x4* __restrict__ src, uint64_t n16)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * kCopyThreads + threadIdx.x;
+    if (i >= n16) return;
+    if constexpr (KIND == SDL_PROBE_COPY_NT) {
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+    } else if constexpr (KIND == SDL_PROBE_READ_NT) {
+        // the data has to be used for the load to stay: one word of dst is written if the 16 bytes spell a
+        // value that seeded or zeroed buffers never hold
+        const u32x4 x = __builtin_nontemporal_load(src + i);
+        if ((x.x ^ x.y ^ x.z ^ x.w) == 0x9e3779b9u && x.x == 0x7f4a7c15u) dst[0] = x;
+    } else {
+        const u32x4 x = {(uint32_t)i, 0u, 0u, 0u};
+        __builtin_nontemporal_store(x, dst + i);
+    }
 }
 
 // ------------------------------------------------------------------ host side
@@ -995,11 +1004,8 @@ size_t code_bytes_at(sdl_format_t fmt, uint64_t elem)
 // w_now), one-pass receive 12 / 8 / 8, merge 16 / 12 / 8 --, the receive side without the merge
 // 16 / 16 / all, and the send side every wavefront it can get.  A single replica: 16 for the fused
 // kernel and the one-pass receive, no cap otherwise.
-// SDL_TUNE_LDS_BYTES in the environment overrides the choice (tuning aid).
 uint32_t lds_cap_bytes(int mode, uint32_t mt, bool aliased)
 {
-    static const int env = [] { const char* e = std::getenv("SDL_TUNE_LDS_BYTES"); return e ? std::atoi(e) : -1; }();
-    if (env >= 0) return (uint32_t)env;
     if (mt == 0) return 0u;
     if (mode == kFused) return mt == 1 ? 10240u : ((aliased || mt == 2) ? 13653u : 20480u);
     if (mode == kReceive) return mt == 1 ? 10240u : (mt == 2 ? 13653u : 20480u);
@@ -1678,16 +1684,32 @@ int sdl_merge_overlap_staged(const sdl_plan_t* plan, uint32_t p, const float* g_
     return merge_fragment(plan, p, g_new_frag, w_now_base, M, alpha, stream, true);
 }
 
-int sdl_copy_bytes(void* dst, const void* src, uint64_t nbytes, void* stream)
+int sdl_memory_probe(sdl_probe_t kind, void* dst, const void* src, uint64_t nbytes, void* stream)
 {
+    if (kind < SDL_PROBE_COPY || kind > SDL_PROBE_FILL_NT) return SDL_ERR_INVALID_ARG;
     if (nbytes == 0) return SDL_OK;
-    if (!dst || !src || nbytes % 16 != 0) return SDL_ERR_INVALID_ARG;
+    if (!dst || (!src && kind != SDL_PROBE_FILL_NT) || nbytes % 16 != 0) return SDL_ERR_INVALID_ARG;
     if (!aligned(dst, 16) || !aligned(src, 16)) return SDL_ERR_ALIGNMENT;
     const uint64_t n16 = nbytes / 16, n_wg = (n16 + kCopyThreads - 1) / kCopyThreads;
     if (n_wg > 0x7fffffffull) return SDL_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(sdl_copy_kernel, dim3((uint32_t)n_wg), dim3(kCopyThreads), 0, (hipStream_t)stream,
-                       static_cast<uint4*>(dst), static_cast<const uint4*>(src), n16);
+    const dim3 grid((uint32_t)n_wg), block(kCopyThreads);
+    hipStream_t s = (hipStream_t)stream;
+    u32x4* d = static_cast<u32x4*>(dst);
+    const u32x4* r = static_cast<const u32x4*>(src);
+    switch (kind) {
+    case SDL_PROBE_COPY:
+        hipLaunchKernelGGL(sdl_copy_kernel, grid, block, 0, s, static_cast<uint4*>(dst), static_cast<const uint4*>(src), n16);
+        break;
+    case SDL_PROBE_COPY_NT: hipLaunchKernelGGL((sdl_probe_kernel<SDL_PROBE_COPY_NT>), grid, block, 0, s, d, r, n16); break;
+    case SDL_PROBE_READ_NT: hipLaunchKernelGGL((sdl_probe_kernel<SDL_PROBE_READ_NT>), grid, block, 0, s, d, r, n16); break;
+    default: hipLaunchKernelGGL((sdl_probe_kernel<SDL_PROBE_FILL_NT>), grid, block, 0, s, d, r, n16); break;
+    }
     return hipGetLastError() == hipSuccess ? SDL_OK : SDL_ERR_DEVICE;
+}
+
+int sdl_copy_bytes(void* dst, const void* src, uint64_t nbytes, void* stream)
+{
+    return sdl_memory_probe(SDL_PROBE_COPY, dst, src, nbytes, stream);
 }
 
 }  // extern "C"

@@ -1,6 +1,6 @@
 // Outer parameters and Nesterov state kept in host memory (Section 2.5 of the paper:
 // only the fragment that is being synchronised needs its outer parameters and outer
-// optimizer state in HBM, "the size of a fragment times two", and since the schedule is
+// optimizer state in HBM, two words per parameter of the fragment, and since the schedule is
 // known in advance the transfer can start early).  This file stages fragments between
 // pinned host arrays and a small pool of device slots with asynchronous copies on a
 // stream of their own, ordered against the compute stream with events.
@@ -21,6 +21,7 @@ struct sdl_offload {
         float* g = nullptr;
         float* mom = nullptr;
         int frag = -1;               // fragment that lives here, -1 = free
+        bool in_use = false;         // handed out by acquire (it may hold updates): only release frees it
         hipEvent_t ready = nullptr;  // host-to-device copy finished
         hipEvent_t done = nullptr;   // compute on the slot finished
     };
@@ -76,6 +77,7 @@ void sdl_offload_destroy(sdl_offload_t* o)
 }
 
 uint64_t sdl_offload_slot_numel(const sdl_offload_t* o) { return o ? o->slot_numel : 0; }
+uint32_t sdl_offload_num_slots(const sdl_offload_t* o) { return o ? (uint32_t)o->slots.size() : 0; }
 
 int sdl_offload_bind(sdl_offload_t* o, float* g_host, float* mom_host, float* const* slot_g, float* const* slot_mom)
 {
@@ -127,33 +129,51 @@ static int copy_fragment(sdl_offload* o, uint32_t p, sdl_offload::Slot& s, bool 
     return SDL_OK;
 }
 
-int sdl_offload_prefetch(sdl_offload_t* o, uint32_t p, void* copy_stream)
+// Starts the copy-in of fragment p into slot `slot` (free, or holding a fragment that was only prefetched).
+static int stage_into(sdl_offload* o, uint32_t p, int slot, void* copy_stream)
 {
-    if (!o || !o->bound || p >= o->P) return SDL_ERR_INVALID_ARG;
-    if (o->slot_of[p] >= 0) return SDL_OK;
-    int free_slot = -1;
-    for (size_t i = 0; i < o->slots.size(); ++i)
-        if (o->slots[i].frag < 0) { free_slot = (int)i; break; }
-    if (free_slot < 0) return SDL_ERR_NOMEM;
-    sdl_offload::Slot& s = o->slots[free_slot];
-    // the write-back of the slot's previous tenant was queued on the same copy stream, so this
-    // copy cannot overtake it
+    sdl_offload::Slot& s = o->slots[slot];
+    if (s.frag >= 0) o->slot_of[s.frag] = -1;      // a prefetched copy that nobody used: dropped, the host arrays are current
+    s.frag = -1;
+    // the write-back of the slot's previous tenant and any earlier copy-in were queued on the same
+    // copy stream, so this copy cannot overtake them
     int rc = copy_fragment(o, p, s, true, (hipStream_t)copy_stream);
     if (rc != SDL_OK) return rc;
     if (hipEventRecord(s.ready, (hipStream_t)copy_stream) != hipSuccess) return SDL_ERR_DEVICE;
     s.frag = (int)p;
-    o->slot_of[p] = free_slot;
+    s.in_use = false;
+    o->slot_of[p] = slot;
     return SDL_OK;
+}
+
+int sdl_offload_prefetch(sdl_offload_t* o, uint32_t p, void* copy_stream)
+{
+    if (!o || !o->bound || p >= o->P) return SDL_ERR_INVALID_ARG;
+    if (o->slot_of[p] >= 0) return SDL_OK;
+    for (size_t i = 0; i < o->slots.size(); ++i)
+        if (o->slots[i].frag < 0) return stage_into(o, p, (int)i, copy_stream);
+    return SDL_ERR_NOMEM;
 }
 
 int sdl_offload_acquire(sdl_offload_t* o, uint32_t p, void* compute_stream, void* copy_stream, float** g_frag,
                         float** mom_frag)
 {
     if (!o || !o->bound || p >= o->P || !g_frag || !mom_frag) return SDL_ERR_INVALID_ARG;
-    int rc = sdl_offload_prefetch(o, p, copy_stream);
-    if (rc != SDL_OK) return rc;
+    if (o->slot_of[p] < 0) {
+        // a free slot, else the slot of a fragment that was prefetched but not acquired yet: its
+        // copy holds nothing the host arrays do not, so it can give way to a fragment that is due now
+        int slot = -1;
+        for (size_t i = 0; i < o->slots.size() && slot < 0; ++i)
+            if (o->slots[i].frag < 0) slot = (int)i;
+        for (size_t i = 0; i < o->slots.size() && slot < 0; ++i)
+            if (!o->slots[i].in_use) slot = (int)i;
+        if (slot < 0) return SDL_ERR_NOMEM;
+        int rc = stage_into(o, p, slot, copy_stream);
+        if (rc != SDL_OK) return rc;
+    }
     sdl_offload::Slot& s = o->slots[o->slot_of[p]];
     if (hipStreamWaitEvent((hipStream_t)compute_stream, s.ready, 0) != hipSuccess) return SDL_ERR_DEVICE;
+    s.in_use = true;
     *g_frag = s.g;
     *mom_frag = s.mom;
     return SDL_OK;
@@ -173,6 +193,7 @@ int sdl_offload_release(sdl_offload_t* o, uint32_t p, void* compute_stream, void
     int rc = write_back(o, p, compute_stream, copy_stream);
     if (rc != SDL_OK) return rc;
     o->slots[o->slot_of[p]].frag = -1;
+    o->slots[o->slot_of[p]].in_use = false;
     o->slot_of[p] = -1;
     return SDL_OK;
 }

@@ -157,6 +157,11 @@ def test_fused_fragment_call_with_messages(fmt, tau):
     ((0, 0), 3, sdl.FMT_E3M0, 1, 0),          # no overlap, a single slot, fetched on demand
     ((5, 5, 5, 5), 4, sdl.FMT_E3M0, 4, 2),    # several fragments in flight at once
     ((1, 4), 2, sdl.FMT_E4M3, 2, 3),
+    # a tight pool and a long look-ahead: one fragment is in flight while later senders are prefetched
+    # early; the fragment that is due next must still find a slot (a prefetched, unused copy gives way)
+    ((2, 2), 4, sdl.FMT_E3M0, 2, 8),
+    ((2, 2), 4, sdl.FMT_E3M0, 1, 11),
+    ((5, 5), 4, sdl.FMT_E3M0, 2, 11),         # two in flight at once, exactly two slots, everything else on demand
 ])
 def test_engine_with_outer_state_in_host_memory(taus, P, fmt, n_slots, lookahead):
     """Section 2.5: outer parameters and momentum live in (pinned) host memory; fragments are
@@ -206,6 +211,34 @@ def test_engine_with_outer_state_in_host_memory(taus, P, fmt, n_slots, lookahead
     assert_f32_close(mom_host.numpy(), ref.mom, "offloaded mom")
     for m in range(M):
         assert_bf16_within_ulp(host_bits(w[m]), ref.w[m], f"offloaded w[{m}]")
+
+
+def test_engine_refuses_a_pool_with_too_few_slots():
+    """With a delay of 5 of every 12 steps and 4 staggered fragments, two fragments are between send and merge at
+    the same time: a pool of one slot is refused when it is bound, not half way through a step."""
+    numel, block, L = _small_model()
+    plan = sdl.sdl_fragment_plan(numel, block, L, 4, sdl.PATTERN_STRIDED, 12, 5)
+    total, M, fmt = plan.total_numel, 2, sdl.FMT_E3M0
+    g, mom, w, _ = workloads.make_span(total, M, tau=0, device=DEV)
+    g_host, mom_host = g.cpu().pin_memory(), mom.cpu().pin_memory()
+    codes, scales = [], []
+    for p in range(4):
+        cb, sb = sdl.sdl_plan_message_bytes(plan, p, fmt)
+        for m in range(M):
+            codes.append(torch.zeros(max(cb, 16), dtype=torch.uint8, device=DEV))
+            scales.append(torch.zeros(max(sb, 16), dtype=torch.uint8, device=DEV))
+    for n_slots, ok in ((1, False), (2, True)):
+        pool = sdl.sdl_offload_create(plan, n_slots)
+        slot_g = [torch.zeros(pool.slot_numel, device=DEV) for _ in range(n_slots)]
+        slot_mom = [torch.zeros(pool.slot_numel, device=DEV) for _ in range(n_slots)]
+        sdl.sdl_offload_bind(pool, g_host, mom_host, slot_g, slot_mom)
+        eng = sdl.sdl_engine_create(plan, 12, (5, 5), fmt, 0.7, 0.9, 0.5)
+        if ok:
+            sdl.sdl_engine_bind_offload(eng, pool, w, codes, scales, copy_stream=torch.cuda.Stream(), lookahead=3)
+        else:
+            with pytest.raises(sdl.SdlError) as e:
+                sdl.sdl_engine_bind_offload(eng, pool, w, codes, scales, copy_stream=torch.cuda.Stream(), lookahead=3)
+            assert e.value.status == -1
 
 
 @pytest.mark.parametrize("taus", [(0, 0, 0), (2, 2, 2)])
