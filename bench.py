@@ -99,6 +99,8 @@ def main() -> int:
     ap.add_argument("--workers", type=int, default=None, help="override M")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the unfused / copy side measurements")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the other target configurations (100M, 4B P=6, 4B P=1, stress) and the stress curve")
     ap.add_argument("--sweep", action="store_true",
                     help="also time the receive side and the fused step over M in {1,2,4,8} x {e3m0,e4m3,bf16}")
     ap.add_argument("--offload", action="store_true",
@@ -188,6 +190,9 @@ def main() -> int:
     }
     if not args.no_extras:
         out["extras"] = extras(st, fmt, wl, M, torch, sdl, args)
+        # the practical ceiling: a non-temporal copy of 1.2 GB (what fraction of it the fused kernel reaches)
+        out["roofline"]["copy_nt_GB/s"] = out["extras"]["memory_probes"]["copy_nt"]["GB/s"]
+        out["roofline"]["frac_of_copy"] = achieved / out["extras"]["memory_probes"]["copy_nt"]["GB/s"]
     if args.sweep:
         out["sweep"] = sweep(st, frag, wl, M, torch, sdl, args)
     if args.offload:
@@ -196,6 +201,13 @@ def main() -> int:
         out["graph"] = graph_timing(step, st, bpp, torch, args)
     if args.engine:
         out["engine"] = engine_timing(st, fmt, wl, M, torch, sdl, workloads)
+    if not args.no_configs and args.workload == "1b" and args.fragment is None and args.format is None \
+            and args.workers is None:
+        # the other target configurations, each timed with the same loop on a state of its own
+        del st, step
+        torch.cuda.empty_cache()
+        out.setdefault("extras", {})
+        out["extras"]["configs"], out["extras"]["stress_curve"] = other_configs(torch, sdl, workloads, args)
     print(json.dumps(out))
     return 0
 
@@ -253,11 +265,28 @@ def extras(st, fmt, wl, M, torch, sdl, args):
     t = time_gpu(torch, lambda: sdl.sdl_fragment_outer_step(g, mom, ws, wn, n, fmt, wl.lr, wl.mu, wl.alpha, None, work),
                  steps, warm)
     res["fused_single_run"] = {"ms": t, "GB/s": algorithmic_bytes_per_param(M, wl.tau) * n / t / 1e6}
-    nbytes = (4 * n) // 16 * 16
-    src = st.g[sl]
-    dst = torch.empty_like(src)
-    t = time_gpu(torch, lambda: sdl.sdl_copy_bytes(dst, src, nbytes), steps, warm)
-    res["copy_kernel"] = {"ms": t, "GB/s": 2 * nbytes / t / 1e6, "bytes": nbytes}
+    res["memory_probes"] = memory_probes(torch, sdl, steps, warm)
+    # the unfused calls once more on the whole fragment (what the schedule driver launches when tau > 0)
+    if fmt != sdl.FMT_E3M0_SPAN:
+        fcb, fsb = sdl.sdl_plan_message_bytes(st.plan, st.fragment, fmt)
+        fc = [torch.empty(max(fcb, 16), dtype=torch.uint8, device="cuda") for _ in range(M)]
+        fs = [torch.empty(max(fsb, 16), dtype=torch.uint8, device="cuda") for _ in range(M)]
+        msg = M * (fcb + fsb)
+        frag_calls = {}
+        for name, fn, nbytes in (
+                ("quantize", lambda: sdl.sdl_quantize_outer_grad_plan(st.plan, st.fragment, st.g, st.w_send, fmt, fc, fs),
+                 (4 + 2 * M) * st.n + msg),
+                ("dequant_reduce_nesterov", lambda: sdl.sdl_dequant_reduce_nesterov_plan(
+                    st.plan, st.fragment, st.g, st.mom, fc, fs, fmt, wl.lr, wl.mu), 16 * st.n + msg),
+                ("merge_overlap", lambda: sdl.sdl_merge_overlap_plan(st.plan, st.fragment, st.g, st.w_now, wl.alpha),
+                 (4 + 4 * M) * st.n),
+                ("receive_outer_step", lambda: sdl.sdl_receive_outer_step_plan(
+                    st.plan, st.fragment, st.g, st.mom, fc, fs, st.w_now, fmt, wl.lr, wl.mu, wl.alpha),
+                 (16 + 4 * M) * st.n + msg)):
+            t = time_gpu(torch, fn, steps, warm)
+            frag_calls[name] = {"ms": t, "GB/s": nbytes / t / 1e6, "frac": nbytes / t / 1e6 / HBM_PEAK_GBS}
+        res["fragment_calls"] = frag_calls
+        del fc, fs
     # parameters handed to evaluation: fp32 mean of the replicas, written as bf16 (2M + 2 bytes per parameter)
     ev = torch.empty(n, dtype=torch.bfloat16, device="cuda")
     t = time_gpu(torch, lambda: sdl.sdl_evaluation_params(sdl.EVAL_REPLICA_MEAN, None, ws, n, ev), steps, warm)
@@ -274,13 +303,55 @@ def extras(st, fmt, wl, M, torch, sdl, args):
     return res
 
 
+def memory_probes(torch, sdl, steps, warm, nbytes=1207959552):
+    """What the memory system gives a kernel that does nothing else, on buffers far larger than the
+    256 MB of Infinity Cache (1.2 GB each): a plain copy, and a copy, a read-only pass and a write-only
+    pass with the non-temporal policy of the method's kernels.  GB/s counts every byte read or written."""
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(2)
+    res = {"bytes": nbytes}
+    for name, kind, traffic in (("copy", sdl.PROBE_COPY, 2 * nbytes), ("copy_nt", sdl.PROBE_COPY_NT, 2 * nbytes),
+                                ("read_nt", sdl.PROBE_READ_NT, nbytes), ("fill_nt", sdl.PROBE_FILL_NT, nbytes)):
+        t = time_gpu(torch, lambda: sdl.sdl_memory_probe(kind, dst, src, nbytes), steps, warm)
+        res[name] = {"ms": t, "GB/s": traffic / t / 1e6}
+    return res
+
+
+def other_configs(torch, sdl, workloads, args):
+    """The target configurations besides the headline one, each on a state of its own that is freed before
+    the next: fused step of the default fragment, same timing loop; then, on the stress state, the curve over
+    replica counts and formats."""
+    configs, curve = {}, None
+    for name in ("100m", "4b_p6", "4b_p1", "stress"):
+        wl = workloads.WORKLOADS[name]
+        frag = DEFAULT_FRAGMENT[name]
+        st = State(wl, sdl, workloads, torch, frag, wl.M)
+        fmt = sdl.FORMATS[wl.fmt]
+        torch.cuda.synchronize()
+        ms = time_gpu(torch, lambda: sdl.sdl_fragment_outer_step_plan(st.plan, frag, st.g, st.mom, st.w_send, st.w_now,
+                                                                      fmt, wl.lr, wl.mu, wl.alpha),
+                      args.steps, args.warmup)
+        bpp = algorithmic_bytes_per_param(wl.M, wl.tau)
+        gbs = bpp * st.n / ms / 1e6
+        configs[name] = {"fragment": frag, "fragment_params": st.n, "M": wl.M, "format": wl.fmt, "tau": wl.tau,
+                         "launches_per_step": -(-len(st.runs) // 16), "ms": ms, "params_per_s": st.n / (ms * 1e-3),
+                         "GB/s": gbs, "frac": gbs / HBM_PEAK_GBS, "algorithmic_bytes_per_param": bpp,
+                         "traffic": MEASURED_TRAFFIC_BYTES.get((name, wl.M, wl.fmt))}
+        if name == "stress":
+            curve = sweep(st, frag, wl, wl.M, torch, sdl, args)
+        del st
+        torch.cuda.empty_cache()
+    return configs, curve
+
+
 def sweep(st, frag, wl, M, torch, sdl, args):
     """Bandwidth curve of the stress configuration: replica counts 1, 2, 4, 8 (up to the M that was
     allocated) and exchange formats E3M0 / E4M3 / BF16, for the receive side alone
     (sdl_dequant_reduce_nesterov_plan: 16 + M*c bytes per parameter) and for the fused step."""
     res = {}
-    steps, warm = max(5, args.steps // 5), 2
-    for fmt_name in ("e3m0", "e4m3", "bf16"):
+    steps, warm = max(10, args.steps // 2), 3
+    # fp32 (no quantisation) rides along as the codec-free reference: same arrays and launch shape, trivial arithmetic
+    for fmt_name in ("e3m0", "e4m3", "bf16", "fp32"):
         f = sdl.FORMATS[fmt_name]
         cb, sb = sdl.sdl_plan_message_bytes(st.plan, frag, f)
         codes = [torch.zeros(max(cb, 16), dtype=torch.uint8, device="cuda") for _ in range(M)]
@@ -293,9 +364,10 @@ def sweep(st, frag, wl, M, torch, sdl, args):
                 st.plan, frag, st.g, st.mom, codes[:m], scales[:m], f, wl.lr, wl.mu), steps, warm)
             t_f = time_gpu(torch, lambda: sdl.sdl_fragment_outer_step_plan(
                 st.plan, frag, st.g, st.mom, st.w_send[:m], st.w_now[:m], f, wl.lr, wl.mu, wl.alpha), steps, warm)
-            res[f"{fmt_name}_M{m}"] = {
-                "reduce_ms": t_r, "reduce_GB/s": (16.0 * st.n + m * (cb + sb)) / t_r / 1e6,
-                "fused_ms": t_f, "fused_GB/s": algorithmic_bytes_per_param(m, wl.tau) * st.n / t_f / 1e6}
+            r_gbs = (16.0 * st.n + m * (cb + sb)) / t_r / 1e6
+            f_gbs = algorithmic_bytes_per_param(m, wl.tau) * st.n / t_f / 1e6
+            res[f"{fmt_name}_M{m}"] = {"reduce_ms": t_r, "reduce_GB/s": r_gbs, "reduce_frac": r_gbs / HBM_PEAK_GBS,
+                                       "fused_ms": t_f, "fused_GB/s": f_gbs, "fused_frac": f_gbs / HBM_PEAK_GBS}
     return res
 
 
