@@ -25,6 +25,7 @@ from .plan import (PATTERN_SEQUENTIAL, PATTERN_STRIDED, UNIT_POST, UNIT_PRE,  # 
 
 FMT_FP32, FMT_BF16, FMT_E4M3, FMT_E3M0 = 0, 1, 2, 3
 FMT_E3M0_B64, FMT_E3M0_B128, FMT_E3M0_SPAN = 4, 5, 6
+FMT_E3M0_RN = 7            # 32-element blocks, block maximum rounded to nearest (scale one binade higher)
 BLOCK = 32
 MAX_BLOCK = 128
 

@@ -52,18 +52,25 @@
 #include <stdlib.h>
 #include <string.h>
 
-/* Exchange formats.  Numbering is this file's own.  The three last ones are E3M0 with
+/* Exchange formats.  Numbering is this file's own.  Formats 4 to 6 are E3M0 with
  * another scale granularity: blocks of 64 or 128 elements, or one scale for the whole span
  * (per tensor), which is what the paper's accounting of exactly 4 bits per parameter
  * suggests.  A whole-span scale is stored as a 4-byte word: the fp32 bit pattern of the
- * span's absolute maximum (the scale byte follows from its exponent field as for blocks). */
+ * span's absolute maximum (the scale byte follows from its exponent field as for blocks).
+ * Format 7 is E3M0 in 32-element blocks with the scale one binade higher, so that the block
+ * maximum a falls into [8, 16) of the code grid and is rounded to nearest like every other
+ * element (2^floor(log2 a) or twice that), instead of into [16, 32) where it always
+ * saturates downwards.  Section 2.4 of the paper says nothing on scaling; both are readings. */
 enum { REF_FMT_FP32 = 0, REF_FMT_BF16 = 1, REF_FMT_E4M3 = 2, REF_FMT_E3M0 = 3,
-       REF_FMT_E3M0_B64 = 4, REF_FMT_E3M0_B128 = 5, REF_FMT_E3M0_SPAN = 6, REF_FMT_COUNT = 7 };
+       REF_FMT_E3M0_B64 = 4, REF_FMT_E3M0_B128 = 5, REF_FMT_E3M0_SPAN = 6, REF_FMT_E3M0_RN = 7,
+       REF_FMT_COUNT = 8 };
 
 #define REF_BLOCK 32u /* elements that share one scale byte in the default formats */
 
 static int is_e3m0(int fmt) { return fmt == REF_FMT_E3M0 || fmt >= REF_FMT_E3M0_B64; }
 static int is_scaled(int fmt) { return fmt == REF_FMT_E4M3 || is_e3m0(fmt); }
+/* exponent of the code grid that the block maximum's binade is mapped to */
+static unsigned elem_emax(int fmt) { return fmt == REF_FMT_E4M3 ? 8u : fmt == REF_FMT_E3M0_RN ? 3u : 4u; }
 /* elements per scale; 0 = the whole span */
 static uint64_t block_of(int fmt)
 {
@@ -135,7 +142,8 @@ static uint32_t block_max_bits(const float* d, uint64_t len)
 }
 
 /* Scale byte for a block whose largest magnitude has biased exponent e_a and
- * whose element format reaches exponent emax (4 for E3M0, 8 for E4M3):
+ * whose binade is mapped to exponent emax of the code grid (4 for E3M0, the grid's largest
+ * value; 3 for the round-to-nearest variant; 8 for E4M3):
  * 2^(sb-127) = 2^(floor(log2 a) - emax), clamped at sb = 0; a zero or
  * fp32-subnormal maximum gives sb = 0; Inf/NaN gives 0xff. */
 static unsigned scale_byte(unsigned e_a, unsigned emax)
@@ -149,7 +157,7 @@ static unsigned scale_byte(unsigned e_a, unsigned emax)
  * magnitude has biased exponent e_a. */
 static unsigned encode_element(float x, unsigned e_a, int fmt)
 {
-    const unsigned emax = is_e3m0(fmt) ? 4u : 8u;
+    const unsigned emax = elem_emax(fmt);
     const unsigned sign_shift = is_e3m0(fmt) ? 3u : 7u;
     const unsigned sb = scale_byte(e_a, emax);
     unsigned s = f32_bits(x) >> 31;
@@ -165,7 +173,7 @@ static unsigned encode_element(float x, unsigned e_a, int fmt)
  * (one per byte, E3M0 in the low 4 bits / E4M3 in all 8) and its scale byte. */
 static unsigned encode_block(const float* d, unsigned len, int fmt, uint8_t* code)
 {
-    const unsigned emax = is_e3m0(fmt) ? 4u : 8u;
+    const unsigned emax = elem_emax(fmt);
     unsigned e_a = block_max_bits(d, len) >> 23;
     for (unsigned i = 0; i < len; ++i) code[i] = (uint8_t)encode_element(d[i], e_a, fmt);
     return scale_byte(e_a, emax);
@@ -199,7 +207,7 @@ size_t sdl_ref_exchange_bytes(int fmt, uint64_t n, size_t* code_bytes, size_t* s
     case REF_FMT_FP32: c = (size_t)n * 4; break;
     case REF_FMT_BF16: c = (size_t)n * 2; break;
     case REF_FMT_E4M3: c = (size_t)n; s = ceil_div(n, REF_BLOCK); break;
-    case REF_FMT_E3M0: case REF_FMT_E3M0_B64: case REF_FMT_E3M0_B128:
+    case REF_FMT_E3M0: case REF_FMT_E3M0_B64: case REF_FMT_E3M0_B128: case REF_FMT_E3M0_RN:
         c = ceil_div(n, 2); s = ceil_div(n, block_of(fmt)); break;
     case REF_FMT_E3M0_SPAN: c = ceil_div(n, 2); s = n ? 4 : 0; break;
     default: break;
@@ -231,7 +239,7 @@ int sdl_ref_quantize_outer_grad(const float* g, const uint16_t* const* w_send, u
         }
         if (is_e3m0(fmt)) memset(codes[m], 0, ceil_div(n, 2));
         const uint64_t block = block_of(fmt) ? block_of(fmt) : (n ? n : 1);
-        const unsigned emax = is_e3m0(fmt) ? 4u : 8u;
+        const unsigned emax = elem_emax(fmt);
         float* d = (float*)malloc((size_t)(block < n ? block : n) * sizeof(float) + 4);
         if (!d) return -5;
         for (uint64_t b0 = 0; b0 < n; b0 += block) {

@@ -346,3 +346,77 @@ def test_per_tensor_scale_is_four_bits_per_parameter():
         ratio = float(dp_tb) / float(ours_tb)
         assert abs(ratio - 100 * 16 / span_bits) / ratio < 0.01          # H = 100 inner steps, 16-bit baseline
         assert abs(ratio - 100 * 16 / block_bits) / ratio > 0.05         # block scaling would not add up
+
+
+# ------------------------------------------------------------------ block maximum rounded to nearest
+
+from oracle import FMT_E3M0_RN   # noqa: E402
+
+
+def test_round_to_nearest_maximum_variant():
+    """E3M0_RN: same codes, same packing, the scale one binade higher (max / scale in [8, 16)).  Pins: the
+    scale byte from the definition, every element by the exact-rational nearest search under that scale,
+    the block maximum decodes to 2^e or 2^(e+1) whichever is nearer (tie at 1.5 * 2^e -> the even code, 8),
+    nothing saturates, and a block whose maximum is doubled by a pilot element has the same codes in the
+    default format (the two conventions differ by that factor of two and nothing else)."""
+    n = 32 * 40
+    g, w = _make(n, 2, seed=31, scale=2e-3)
+    g[7] += 0.25
+    codes, scales = oracle.quantize_outer_grad(g, w, FMT_E3M0_RN)
+    assert oracle.exchange_bytes(FMT_E3M0_RN, n) == oracle.exchange_bytes(FMT_E3M0, n) == (n // 2, n // 32)
+    for m in range(2):
+        d = _delta_of(g, w[m])
+        got = oracle.unpack_e3m0(codes[m], n)
+        for b0 in range(0, n, 32):
+            blk = d[b0:b0 + 32]
+            a = np.abs(blk).max()
+            e_a = int(np.float32(a).view(np.uint32) >> 23)
+            sb = max(e_a - 3, 0)
+            assert scales[m][b0 // 32] == sb
+            top = Fraction(float(a)) / Fraction(2) ** (sb - 127)
+            assert 8 <= top < 16
+            for i in range(32):
+                y = Fraction(abs(float(blk[i]))) / Fraction(2) ** (sb - 127)
+                assert got[b0 + i] & 7 == _exact_e3m0(y), (m, b0, i)
+                assert got[b0 + i] >> 3 == int(np.signbit(blk[i]))
+            i_top = int(np.abs(blk).argmax())
+            dec = abs(oracle.decode_code(int(got[b0 + i_top]), sb, FMT_E3M0_RN))
+            lo = 2.0 ** (e_a - 127)
+            assert dec == (lo if top <= 12 else 2 * lo)
+            # the same block with a pilot element of twice the maximum, in the default format: the
+            # scale is the same, so are the codes of the original elements
+            pilot = np.concatenate([blk[:31], np.float32([2 * a])]).astype(np.float32)
+            c_def, sb_def = oracle.encode_block(pilot, FMT_E3M0)
+            assert sb_def == sb
+            assert np.array_equal(c_def[:31], got[b0:b0 + 31])
+    # decode is the default format's decode
+    for code in range(16):
+        for sb in (0, 1, 100, 127, 254, 255):
+            a, b = oracle.decode_code(code, sb, FMT_E3M0_RN), oracle.decode_code(code, sb, FMT_E3M0)
+            assert (a == b) or (a != a and b != b)
+
+
+def test_round_to_nearest_maximum_tie_and_powers_of_two():
+    # a block whose maximum is exactly 1.5 * 2^k: tie between 8 and 16 -> even code 6 (value 8)
+    blk = np.zeros(32, np.float32)
+    blk[3] = 1.5 * 2.0 ** -9
+    blk[4] = -(2.0 ** -9)
+    blk[5] = 2.0 ** -14           # 5 binades below the maximum's binade: the smallest magnitude, 1/4 of the scale
+    blk[6] = 2.0 ** -15           # exactly half of it: tie with zero -> even code 0
+    blk[8] = 2.0 ** -15 * 1.0000001
+    c, sb = oracle.encode_block(blk, FMT_E3M0_RN)
+    assert sb == (127 - 9) - 3
+    assert list(c[[3, 4, 5, 6, 8]]) == [6, 8 | 6, 1, 0, 1]
+    for i in (4, 5):
+        assert oracle.decode_code(int(c[i]), sb, FMT_E3M0_RN) == blk[i]
+    # the whole step accepts the format and the fused step equals the three calls
+    g, w = _make(4096 + 37, 3, seed=33)
+    wn = [x.copy() for x in w]
+    g2, m2 = g.copy(), np.zeros_like(g)
+    g3, m3, w3 = g.copy(), np.zeros_like(g), [x.copy() for x in w]
+    oracle.fragment_outer_step(g2, m2, w, wn, FMT_E3M0_RN, 0.7, 0.9, 0.5)
+    rc, rs = oracle.quantize_outer_grad(g3, w, FMT_E3M0_RN)
+    oracle.dequant_reduce_nesterov(g3, m3, rc, rs, FMT_E3M0_RN, 0.7, 0.9)
+    oracle.merge_overlap(g3, w3, 0.5)
+    assert np.array_equal(g2, g3) and np.array_equal(m2, m3)
+    assert all(np.array_equal(a, b) for a, b in zip(wn, w3))

@@ -29,6 +29,8 @@ MUTANTS = [
     ("E4M3 subnormal quantum wrong", "ldexp((double)m, -9)", "ldexp((double)m, -8)"),
     ("sign bit dropped", "unsigned s = f32_bits(x) >> 31;", "unsigned s = 0; (void)x;"),
     ("momentum not decayed", "float mu_mom = mu * mom[i];", "float mu_mom = mom[i];"),
+    ("round-to-nearest variant uses the default scale", "fmt == REF_FMT_E3M0_RN ? 3u : 4u", "fmt == REF_FMT_E3M0_RN ? 4u : 4u"),
+    ("round-to-nearest variant two binades up", "fmt == REF_FMT_E3M0_RN ? 3u : 4u", "fmt == REF_FMT_E3M0_RN ? 2u : 4u"),
     ("block maximum skips the last element", "for (uint64_t i = 0; i < len; ++i) {\n        uint32_t m = f32_bits(d[i]) & 0x7fffffffu;", "for (uint64_t i = 0; i + 1 < len; ++i) {\n        uint32_t m = f32_bits(d[i]) & 0x7fffffffu;"),
 ]
 
@@ -37,6 +39,7 @@ def test_the_unmodified_source_contains_every_mutation_site():
     text = open(SRC).read()
     for name, old, _new in MUTANTS:
         assert text.count(old) == 1, (name, text.count(old))
+
 
 
 @pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])

@@ -4,9 +4,9 @@ grid.  The reading built here puts max|x| / scale into [16, 32), so the maximum 
 at 16 (rounded towards zero, error between 0 and -50 %) while every other element is rounded to
 nearest.  The alternative puts it into [8, 16), where the maximum is rounded to nearest as well but
 every element loses one binade at the small end.  This file measures both on the input recipes, with a
-plain nearest-value search written out here; for the built reading the search must agree with the
-oracle bit for bit (so it is one more pin of the oracle's encoder), and the numbers it prints are the
-ones quoted in the design notes."""
+plain nearest-value search written out here; both conventions are formats of the oracle (E3M0 and
+E3M0_RN) and the search must agree with each bit for bit (so it is one more pin of the oracle's
+encoder); the numbers it prints are the ones quoted in the design notes."""
 import numpy as np
 import pytest
 import torch
@@ -44,16 +44,18 @@ def _deltas(kind, n, M, seed=0):
     return hg, hs, d
 
 
+@pytest.mark.parametrize("fmt,emax", [(oracle.FMT_E3M0, 4), (oracle.FMT_E3M0_RN, 3)])
 @pytest.mark.parametrize("kind", ["normal", "student_t3", "outliers"])
-def test_search_with_the_built_convention_is_the_oracle(kind):
+def test_search_is_the_oracle(kind, fmt, emax):
+    """Both conventions exist as formats of the oracle; the search above must reproduce each bit for bit."""
     n, M = 1 << 15, 2
     hg, hs, d = _deltas(kind, n, M)
-    codes, scales = oracle.quantize_outer_grad(hg, hs, oracle.FMT_E3M0)
+    codes, scales = oracle.quantize_outer_grad(hg, hs, fmt)
     for m in range(M):
         nib = oracle.unpack_e3m0(codes[m], n)
         mag = np.where((nib & 7) == 0, 0.0, np.exp2((nib & 7).astype(np.float64) - 3))
         dec = np.where(nib & 8, -mag, mag) * np.exp2(np.repeat(scales[m].astype(np.float64), 32) - 127)
-        assert np.array_equal(dec, _fake_quant(d[m], 4)), kind
+        assert np.array_equal(dec, _fake_quant(d[m], emax)), kind
 
 
 @pytest.mark.parametrize("kind", ["normal", "student_t3", "outliers"])
