@@ -95,7 +95,7 @@ def main() -> int:
     ap.add_argument("--workload", default="1b", choices=sorted(DEFAULT_FRAGMENT))
     ap.add_argument("--fragment", type=int, default=None)
     ap.add_argument("--format", default=None,
-                    choices=["e3m0", "e4m3", "bf16", "fp32", "e3m0_b64", "e3m0_b128", "e3m0_span"])
+                    choices=["e3m0", "e4m3", "bf16", "fp32", "e3m0_b64", "e3m0_b128", "e3m0_span", "e3m0_rn"])
     ap.add_argument("--workers", type=int, default=None, help="override M")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the unfused / copy side measurements")

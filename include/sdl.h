@@ -92,9 +92,16 @@ typedef enum {
  *                              scale array of a span is one 4-byte word (4-byte aligned): the
  *                              fp32 bit pattern of the span's absolute maximum, from whose
  *                              exponent field the scale byte follows as above.  It is produced
- *                              by an extra pass over g and w_send (a grid-wide maximum). */
+ *                              by an extra pass over g and w_send (a grid-wide maximum).
+ * E3M0 with the other choice of scale (Section 2.4 is silent on scaling; codes, packing and 32-element
+ * blocks as SDL_FMT_E3M0):
+ *   SDL_FMT_E3M0_RN            emax = 3: the scale is one binade higher, so the block maximum a falls
+ *                              into [8, 16) of the code grid and is rounded to nearest like every other
+ *                              element (to 2^floor(log2 a) or twice that) instead of always saturating
+ *                              downwards; one binade less at the small end.  The smaller error of the
+ *                              decoded mean on heavy-tailed outer gradients. */
 typedef enum { SDL_FMT_FP32 = 0, SDL_FMT_BF16 = 1, SDL_FMT_E4M3 = 2, SDL_FMT_E3M0 = 3,
-               SDL_FMT_E3M0_B64 = 4, SDL_FMT_E3M0_B128 = 5, SDL_FMT_E3M0_SPAN = 6 } sdl_format_t;
+               SDL_FMT_E3M0_B64 = 4, SDL_FMT_E3M0_B128 = 5, SDL_FMT_E3M0_SPAN = 6, SDL_FMT_E3M0_RN = 7 } sdl_format_t;
 
 /* Fragment patterns of Section 2.2: interleaved blocks (default) or consecutive blocks. */
 typedef enum { SDL_PATTERN_STRIDED = 0, SDL_PATTERN_SEQUENTIAL = 1 } sdl_pattern_t;

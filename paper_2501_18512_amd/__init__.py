@@ -16,9 +16,10 @@ from typing import List, Optional, Sequence, Tuple
 import torch
 
 FMT_FP32, FMT_BF16, FMT_E4M3, FMT_E3M0 = 0, 1, 2, 3
-FMT_E3M0_B64, FMT_E3M0_B128, FMT_E3M0_SPAN = 4, 5, 6
+FMT_E3M0_B64, FMT_E3M0_B128, FMT_E3M0_SPAN, FMT_E3M0_RN = 4, 5, 6, 7
 FORMATS = {"fp32": FMT_FP32, "bf16": FMT_BF16, "e4m3": FMT_E4M3, "e3m0": FMT_E3M0,
-           "e3m0_b64": FMT_E3M0_B64, "e3m0_b128": FMT_E3M0_B128, "e3m0_span": FMT_E3M0_SPAN}
+           "e3m0_b64": FMT_E3M0_B64, "e3m0_b128": FMT_E3M0_B128, "e3m0_span": FMT_E3M0_SPAN,
+           "e3m0_rn": FMT_E3M0_RN}
 PATTERN_STRIDED, PATTERN_SEQUENTIAL = 0, 1
 UNIT_PRE, UNIT_POST = -1, -2
 MAX_WORKERS = 16

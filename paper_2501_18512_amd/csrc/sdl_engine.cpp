@@ -47,7 +47,7 @@ int sdl_engine_create(const sdl_plan_t* plan, uint32_t H, uint32_t M, const uint
                       float lr, float mu, float alpha, sdl_engine_t** out)
 {
     if (!plan || !out || !tau_m || M == 0 || M > SDL_MAX_WORKERS || H == 0) return SDL_ERR_INVALID_ARG;
-    if (fmt < SDL_FMT_FP32 || fmt > SDL_FMT_E3M0_SPAN) return SDL_ERR_INVALID_ARG;
+    if (fmt < SDL_FMT_FP32 || fmt > SDL_FMT_E3M0_RN) return SDL_ERR_INVALID_ARG;
     for (uint32_t m = 0; m < M; ++m)
         if (tau_m[m] >= H) return SDL_ERR_INVALID_ARG;
     sdl_engine* e = nullptr;

@@ -186,7 +186,8 @@ __device__ __forceinline__ BlockScale block_scale_from_exponent(uint32_t e_a)
 {
     // written with single comparisons and selects: this runs once per scale block and replica,
     // and as control flow it cost more than the codec of the block's elements
-    constexpr uint32_t emax = is_e3m0(FMT) ? 4u : 8u;
+    // exponent of the code grid that the block maximum's binade is mapped to
+    constexpr uint32_t emax = FMT == SDL_FMT_E4M3 ? 8u : FMT == SDL_FMT_E3M0_RN ? 3u : 4u;
     BlockScale b;
     const uint32_t sb = e_a > emax ? e_a - emax : 0u;
     const bool nan_block = e_a == 255u;
@@ -1106,11 +1107,12 @@ hipError_t launch(const Args& a, sdl_format_t fmt, uint32_t n_wg, hipStream_t s)
     case SDL_FMT_E3M0_B64: return launch_f<MODE, SDL_FMT_E3M0_B64>(a, n_wg, s);
     case SDL_FMT_E3M0_B128: return launch_f<MODE, SDL_FMT_E3M0_B128>(a, n_wg, s);
     case SDL_FMT_E3M0_SPAN: return launch_f<MODE, SDL_FMT_E3M0_SPAN>(a, n_wg, s);
+    case SDL_FMT_E3M0_RN: return launch_f<MODE, SDL_FMT_E3M0_RN>(a, n_wg, s);
     default: return launch_f<MODE, SDL_FMT_E3M0>(a, n_wg, s);
     }
 }
 
-bool valid_format(sdl_format_t fmt) { return fmt >= SDL_FMT_FP32 && fmt <= SDL_FMT_E3M0_SPAN; }
+bool valid_format(sdl_format_t fmt) { return fmt >= SDL_FMT_FP32 && fmt <= SDL_FMT_E3M0_RN; }
 
 // 16-byte alignment of a call's pointers: model = g, mom and the replicas; msg = codes (scale
 // bytes need none).

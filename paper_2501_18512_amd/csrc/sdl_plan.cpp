@@ -176,7 +176,7 @@ size_t sdl_exchange_bytes(sdl_format_t fmt, uint64_t numel, size_t* code_bytes, 
     case SDL_FMT_FP32: c = (size_t)numel * 4; break;
     case SDL_FMT_BF16: c = (size_t)numel * 2; break;
     case SDL_FMT_E4M3: c = (size_t)numel; s = blocks; break;
-    case SDL_FMT_E3M0: c = (size_t)((numel + 1) / 2); s = blocks; break;
+    case SDL_FMT_E3M0: case SDL_FMT_E3M0_RN: c = (size_t)((numel + 1) / 2); s = blocks; break;
     case SDL_FMT_E3M0_B64: c = (size_t)((numel + 1) / 2); s = (size_t)((numel + 63) / 64); break;
     case SDL_FMT_E3M0_B128: c = (size_t)((numel + 1) / 2); s = (size_t)((numel + 127) / 128); break;
     case SDL_FMT_E3M0_SPAN: c = (size_t)((numel + 1) / 2); s = numel ? 4 : 0; break;

@@ -12,7 +12,7 @@ import paper_2501_18512_amd as sdl
 import workloads
 
 RTOL, ATOL = 1e-6, 1e-7
-FMT_NAMES = {0: "fp32", 1: "bf16", 2: "e4m3", 3: "e3m0", 4: "e3m0_b64", 5: "e3m0_b128", 6: "e3m0_span"}
+FMT_NAMES = {0: "fp32", 1: "bf16", 2: "e4m3", 3: "e3m0", 4: "e3m0_b64", 5: "e3m0_b128", 6: "e3m0_span", 7: "e3m0_rn"}
 
 
 def host_f32(t):

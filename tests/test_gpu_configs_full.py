@@ -59,7 +59,7 @@ def _three_paths(model, p, fmt, capsys, what):
                         w_now0=wn0, variants=variants, what=what, progress=_progress(capsys))
 
 
-@pytest.mark.parametrize("fmt", ["e3m0", "e3m0_span", "e3m0_b64", "e3m0_b128"])
+@pytest.mark.parametrize("fmt", ["e3m0", "e3m0_span", "e3m0_b64", "e3m0_b128", "e3m0_rn"])
 def test_config_1b_fragment_every_element(fmt, capsys):
     wl = workloads.WORKLOADS["1b"]
     model = FlatModel(wl, fill_fragments=[1])
@@ -67,7 +67,7 @@ def test_config_1b_fragment_every_element(fmt, capsys):
     counts = _three_paths(model, 1, sdl.FORMATS[fmt], capsys, f"1b f1 {fmt}")
     assert counts["elements"] == 302014464
     assert counts["code_bytes"] == 2 * wl.M * 302014464 // 2          # two message-writing paths, 4 replicas
-    block = {"e3m0": 32, "e3m0_b64": 64, "e3m0_b128": 128}.get(fmt)
+    block = {"e3m0": 32, "e3m0_rn": 32, "e3m0_b64": 64, "e3m0_b128": 128}.get(fmt)
     assert counts["scale_bytes"] == (2 * wl.M * 302014464 // block if block else 2 * wl.M * 4 * 48)
 
 

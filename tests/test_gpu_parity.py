@@ -16,7 +16,7 @@ DEV = "cuda"
 LR, MU = 0.7, 0.9
 SIZES = [1, 7, 8, 31, 32, 33, 255, 2047, 2048, 2049, 3 * 2048 + 77, 20000 + 13]
 FMTS = [sdl.FMT_E3M0, sdl.FMT_E4M3, sdl.FMT_BF16, sdl.FMT_FP32, sdl.FMT_E3M0_B64, sdl.FMT_E3M0_B128,
-        sdl.FMT_E3M0_SPAN]
+        sdl.FMT_E3M0_SPAN, sdl.FMT_E3M0_RN]
 
 
 def _span(n, M, tau=1, delta="normal", seed=0):
@@ -61,7 +61,7 @@ def test_dequant_reduce_nesterov(fmt, M):
         assert_f32_close(host_f32(mom), hmom, f"mom n={n}")
 
 
-@pytest.mark.parametrize("fmt", [sdl.FMT_E3M0, sdl.FMT_E4M3, sdl.FMT_E3M0_B64, sdl.FMT_E3M0_B128])
+@pytest.mark.parametrize("fmt", [sdl.FMT_E3M0, sdl.FMT_E4M3, sdl.FMT_E3M0_B64, sdl.FMT_E3M0_B128, sdl.FMT_E3M0_RN])
 @pytest.mark.parametrize("M", [1, 3])
 def test_receive_side_decodes_every_code_and_scale(fmt, M):
     """Messages are plain bytes: whatever a peer sends is decoded like the oracle decodes it,

@@ -18,7 +18,7 @@ from gpu_util import (HostCopy, assert_bf16_within_ulp, assert_bytes_equal, asse
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
 FMTS = [sdl.FMT_E3M0, sdl.FMT_E4M3, sdl.FMT_BF16, sdl.FMT_FP32, sdl.FMT_E3M0_B64, sdl.FMT_E3M0_B128,
-        sdl.FMT_E3M0_SPAN]
+        sdl.FMT_E3M0_SPAN, sdl.FMT_E3M0_RN]
 PAD = 512        # message and staging layouts pad every piece to a multiple of 512 elements
 
 
