@@ -30,12 +30,12 @@ DEFAULT_FRAGMENT = {"tiny": 0, "100m": 1, "1b": 1, "4b_p6": 1, "4b_p1": 0, "stre
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by
 # the reading of the copy kernel); see profiles/.  None = not measured for that workload.
 MEASURED_TRAFFIC_BYTES = {     # (workload, M, format), default fragment of the workload
-    # profiles/fused_e3m0_1b_m4_hbm_traffic.txt: 7.2480e9 B fetched + 4.8322e9 B written per launch
-    ("1b", 4, "e3m0"): 12.0802e9,
-    # profiles/fused_e3m0_other_workloads_hbm_traffic.txt
-    ("stress", 8, "e3m0"): 19.3283e9,
-    ("4b_p6", 2, "e3m0"): 19.0263e9,
-    ("100m", 2, "e3m0"): 0.79297e9,
+    # profiles/fused_all_configs_hbm_traffic.txt: bytes fetched + bytes written per launch
+    ("1b", 4, "e3m0"): 7.2483e9 + 4.8322e9,
+    ("stress", 8, "e3m0"): 12.0806e9 + 7.2483e9,
+    ("4b_p6", 2, "e3m0"): 10.8721e9 + 8.1543e9,
+    ("4b_p1", 2, "e3m0"): 68.3781e9 + 51.2844e9,
+    ("100m", 2, "e3m0"): 0.4531e9 + 0.3399e9,
 }
 
 
@@ -45,9 +45,10 @@ def algorithmic_bytes_per_param(M: int, tau: int) -> float:
 
 
 class State:
-    """Flat model arrays in HBM and the plan of one workload."""
+    """Flat model arrays in HBM and the plan of one workload.  The arrays are carved from one allocation as
+    sdl_flat_layout says (what the library recommends); separate=True allocates them one by one instead."""
 
-    def __init__(self, wl, sdl, workloads, torch, fragment: int, M: int):
+    def __init__(self, wl, sdl, workloads, torch, fragment: int, M: int, separate: bool = False):
         self.wl, self.M, self.fragment = wl, M, fragment
         dev = "cuda"
         if wl.shape is None:
@@ -58,11 +59,14 @@ class State:
             L = shape.n_layers
         self.plan = sdl.sdl_fragment_plan(numel, block, L, wl.P, sdl.PATTERN_STRIDED, wl.H, wl.tau)
         total = self.plan.total_numel
-        self.g = torch.empty(total, dtype=torch.float32, device=dev)
-        self.mom = torch.empty(total, dtype=torch.float32, device=dev)
-        self.w_send = [torch.empty(total, dtype=torch.bfloat16, device=dev) for _ in range(M)]
-        self.w_now = self.w_send if wl.tau == 0 else \
-            [torch.empty(total, dtype=torch.bfloat16, device=dev) for _ in range(M)]
+        if separate:
+            self.g = torch.empty(total, dtype=torch.float32, device=dev)
+            self.mom = torch.empty(total, dtype=torch.float32, device=dev)
+            self.w_send = [torch.empty(total, dtype=torch.bfloat16, device=dev) for _ in range(M)]
+            self.w_now = self.w_send if wl.tau == 0 else \
+                [torch.empty(total, dtype=torch.bfloat16, device=dev) for _ in range(M)]
+        else:
+            self.g, self.mom, self.w_send, self.w_now, self.pool = sdl.alloc_flat_model(total, M, wl.tau > 0, device=dev)
         self.spans = sdl.sdl_plan_fragment_spans(self.plan, fragment)
         self.runs = sdl.sdl_plan_fragment_runs(self.plan, fragment)
         self.n = sum(n for _, n, _ in self.spans)
@@ -98,6 +102,8 @@ def main() -> int:
                     choices=["e3m0", "e4m3", "bf16", "fp32", "e3m0_b64", "e3m0_b128", "e3m0_span", "e3m0_rn"])
     ap.add_argument("--workers", type=int, default=None, help="override M")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate-allocations", action="store_true",
+                    help="allocate every flat array on its own instead of carving them from one allocation")
     ap.add_argument("--no-extras", action="store_true", help="skip the unfused / copy side measurements")
     ap.add_argument("--no-configs", action="store_true",
                     help="skip the other target configurations (100M, 4B P=6, 4B P=1, stress) and the stress curve")
@@ -128,7 +134,7 @@ def main() -> int:
     fmt_name = args.format or wl.fmt
     fmt = sdl.FORMATS[fmt_name]
     frag = DEFAULT_FRAGMENT[args.workload] if args.fragment is None else args.fragment
-    st = State(wl, sdl, workloads, torch, frag, M)
+    st = State(wl, sdl, workloads, torch, frag, M, separate=args.separate_allocations)
     torch.cuda.synchronize()
 
     # ---- CPU baseline sample is taken from the untouched inputs (before any GPU step)
@@ -177,6 +183,8 @@ def main() -> int:
                         f"tau={wl.tau}, alpha={wl.alpha}, lr={wl.lr}, mu={wl.mu}, deltas={wl.delta}",
             "fragment_params": st.n, "M": M, "format": fmt_name, "tau": wl.tau, "alpha": wl.alpha,
             "launches_per_step": n_launch,
+            "array_layout": "separate allocations" if args.separate_allocations else
+                            "one allocation, sdl_flat_layout (2 MiB slots, bases staggered by 32 KiB)",
         },
         "roofline": {
             "bound": "hbm", "kernel": kernel_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
@@ -322,10 +330,13 @@ def other_configs(torch, sdl, workloads, args):
     the next: fused step of the default fragment, same timing loop; then, on the stress state, the curve over
     replica counts and formats."""
     configs, curve = {}, None
-    for name in ("100m", "4b_p6", "4b_p1", "stress"):
-        wl = workloads.WORKLOADS[name]
-        frag = DEFAULT_FRAGMENT[name]
-        st = State(wl, sdl, workloads, torch, frag, wl.M)
+    # "1b_separate_allocations": the headline workload once more with every array allocated on its own, which is
+    # how a caller that does not follow sdl_flat_layout holds them
+    for name in ("1b_separate_allocations", "100m", "4b_p6", "4b_p1", "stress"):
+        separate = name.endswith("_separate_allocations")
+        wl = workloads.WORKLOADS[name.split("_separate")[0]]
+        frag = DEFAULT_FRAGMENT[wl.name]
+        st = State(wl, sdl, workloads, torch, frag, wl.M, separate=separate)
         fmt = sdl.FORMATS[wl.fmt]
         torch.cuda.synchronize()
         ms = time_gpu(torch, lambda: sdl.sdl_fragment_outer_step_plan(st.plan, frag, st.g, st.mom, st.w_send, st.w_now,
@@ -336,7 +347,7 @@ def other_configs(torch, sdl, workloads, args):
         configs[name] = {"fragment": frag, "fragment_params": st.n, "M": wl.M, "format": wl.fmt, "tau": wl.tau,
                          "launches_per_step": -(-len(st.runs) // 16), "ms": ms, "params_per_s": st.n / (ms * 1e-3),
                          "GB/s": gbs, "frac": gbs / HBM_PEAK_GBS, "algorithmic_bytes_per_param": bpp,
-                         "traffic": MEASURED_TRAFFIC_BYTES.get((name, wl.M, wl.fmt))}
+                         "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, wl.M, wl.fmt))}
         if name == "stress":
             curve = sweep(st, frag, wl, wl.M, torch, sdl, args)
         del st

@@ -111,6 +111,7 @@ def _load() -> ctypes.CDLL:
     lib.sdl_engine_bind_offload.argtypes = [vp, vp, pp, pp, pp, vp, u32]
     lib.sdl_copy_bytes.argtypes = [vp, vp, u64, vp]
     lib.sdl_memory_probe.argtypes = [ctypes.c_int, vp, vp, u64, vp]
+    lib.sdl_flat_layout.argtypes = [u64, u32, ctypes.c_int, ctypes.POINTER(u64), ctypes.POINTER(u64)]
     lib.sdl_engine_track_cosine.argtypes = [vp, pp, vp, vp, ctypes.c_size_t]
     lib.sdl_evaluation_params.argtypes = [ctypes.c_int, vp, pp, u32, u64, vp, vp]
     lib.sdl_cosine_workspace_bytes.argtypes = [u32, u32]
@@ -591,6 +592,33 @@ def sdl_engine_track_cosine(engine: "Engine", span_results, fragment_results, wo
                                         workspace.numel() if workspace is not None else 0),
            "sdl_engine_track_cosine")
     engine._keep_cosine = (span_results, fragment_results, workspace)
+
+
+def sdl_flat_layout(total_numel: int, M: int, separate_w_now: bool) -> Tuple[List[int], int]:
+    """Byte offsets of g, mom, w_send[0..M) (, w_now[0..M)) inside one allocation, and its size."""
+    n = 2 + (2 if separate_w_now else 1) * M
+    offs = (ctypes.c_uint64 * n)()
+    size = ctypes.c_uint64()
+    _check(_lib.sdl_flat_layout(total_numel, M, int(separate_w_now), offs, ctypes.byref(size)), "sdl_flat_layout")
+    return list(offs), size.value
+
+
+def alloc_flat_model(total_numel: int, M: int, separate_w_now: bool, device="cuda"):
+    """The flat model arrays carved from one device allocation as sdl_flat_layout says (allocation only, the
+    contents are uninitialised).  Returns (g, mom, w_send, w_now, pool); w_now is w_send itself when there is
+    no overlap delay.  Keep `pool` alive as long as the views."""
+    offs, size = sdl_flat_layout(total_numel, M, separate_w_now)
+    align = 1 << 21
+    pool = torch.empty(size + align, dtype=torch.uint8, device=device)
+    base = (-pool.data_ptr()) % align
+
+    def view(k, dtype, width):
+        return pool[base + offs[k]: base + offs[k] + total_numel * width].view(dtype)
+
+    g, mom = view(0, torch.float32, 4), view(1, torch.float32, 4)
+    w_send = [view(2 + m, torch.bfloat16, 2) for m in range(M)]
+    w_now = [view(2 + M + m, torch.bfloat16, 2) for m in range(M)] if separate_w_now else w_send
+    return g, mom, w_send, w_now, pool
 
 
 def alloc_exchange(fmt: int, n: int, M: int, device="cuda"):

@@ -187,6 +187,21 @@ size_t sdl_exchange_bytes(sdl_format_t fmt, uint64_t numel, size_t* code_bytes, 
     return c + s;
 }
 
+int sdl_flat_layout(uint64_t total_numel, uint32_t M, int separate_w_now, uint64_t* offsets, uint64_t* total_bytes)
+{
+    if (!offsets || !total_bytes || M == 0 || M > SDL_MAX_WORKERS) return SDL_ERR_INVALID_ARG;
+    const uint32_t n_arrays = 2u + (separate_w_now ? 2u : 1u) * M;
+    uint64_t slot = 0;       // start of the next 2 MiB-aligned slot
+    for (uint32_t k = 0; k < n_arrays; ++k) {
+        const uint64_t bytes = total_numel * (k < 2 ? 4u : 2u);
+        offsets[k] = slot + (uint64_t)k * SDL_LAYOUT_STAGGER;
+        const uint64_t end = offsets[k] + bytes;
+        slot = (end + SDL_LAYOUT_SLOT_ALIGN - 1) / SDL_LAYOUT_SLOT_ALIGN * SDL_LAYOUT_SLOT_ALIGN;
+    }
+    *total_bytes = slot;
+    return SDL_OK;
+}
+
 const char* sdl_status_string(int status)
 {
     switch (status) {

@@ -119,11 +119,9 @@ class FlatModel:
         self.plan = sdl.sdl_fragment_plan(self.numel, self.block, self.L, wl.P, sdl.PATTERN_STRIDED,
                                           wl.H, wl.tau)
         total = self.plan.total_numel
-        self.g = torch.empty(total, dtype=torch.float32, device=device)
-        self.mom = torch.empty(total, dtype=torch.float32, device=device)
-        self.w_send = [torch.empty(total, dtype=torch.bfloat16, device=device) for _ in range(wl.M)]
-        self.w_now = self.w_send if wl.tau == 0 else \
-            [torch.empty(total, dtype=torch.bfloat16, device=device) for _ in range(wl.M)]
+        # one allocation, carved as the library recommends: the layout bench.py times
+        self.g, self.mom, self.w_send, self.w_now, self.pool = sdl.alloc_flat_model(total, wl.M, wl.tau > 0,
+                                                                                    device=device)
         frags = range(wl.P) if fill_fragments is None else fill_fragments
         for p in frags:
             self.fill_fragment(p)

@@ -240,3 +240,18 @@ def test_evaluation_params_rejects_bad_arguments_before_launch():
     assert call(sdl.EVAL_REPLICA_MEAN, 0, ptrs([good]), 1, 64, good + 1, 0) == -3
     assert call(sdl.EVAL_OUTER, good, None, 0, (2 ** 31) * 512, good, 0) == -2     # beyond the supported size
     assert call(sdl.EVAL_REPLICA_MEAN, 0, None, 2, 0, 0, 0) == 0                   # nothing to do
+
+
+def test_flat_layout_carves_disjoint_staggered_arrays():
+    for total, M, sep in ((1000, 2, False), (1339131904, 4, True), (4273695744, 16, True), (0, 1, True)):
+        offs, size = sdl.sdl_flat_layout(total, M, sep)
+        assert len(offs) == 2 + (2 if sep else 1) * M
+        ends = [o + total * (4 if k < 2 else 2) for k, o in enumerate(offs)]
+        for k, o in enumerate(offs):
+            assert o % (1 << 21) == k * 32768            # a 2 MiB slot plus the stagger: 128-byte aligned as well
+            if k:
+                assert o >= ends[k - 1]                  # disjoint, in order
+        assert size >= ends[-1] and size % (1 << 21) == 0
+    for bad_M in (0, 17):
+        with pytest.raises(sdl.SdlError):
+            sdl.sdl_flat_layout(1000, bad_M, True)
