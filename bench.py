@@ -315,8 +315,12 @@ def memory_probes(torch, sdl, steps, warm, nbytes=1207959552):
     """What the memory system gives a kernel that does nothing else, on buffers far larger than the
     256 MB of Infinity Cache (1.2 GB each): a plain copy, and a copy, a read-only pass and a write-only
     pass with the non-temporal policy of the method's kernels.  GB/s counts every byte read or written."""
-    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
-    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(2)
+    # both buffers in one allocation, 2 MiB-aligned slots with a 32 KiB stagger, like the model arrays
+    slot = (nbytes + (1 << 21) - 1) // (1 << 21) * (1 << 21)
+    pool = torch.empty(2 * slot + (1 << 22), dtype=torch.uint8, device="cuda")
+    base = (-pool.data_ptr()) % (1 << 21)
+    src = pool[base:base + nbytes].fill_(1)
+    dst = pool[base + slot + 32768:base + slot + 32768 + nbytes].fill_(2)
     res = {"bytes": nbytes}
     for name, kind, traffic in (("copy", sdl.PROBE_COPY, 2 * nbytes), ("copy_nt", sdl.PROBE_COPY_NT, 2 * nbytes),
                                 ("read_nt", sdl.PROBE_READ_NT, nbytes), ("fill_nt", sdl.PROBE_FILL_NT, nbytes)):

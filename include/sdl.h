@@ -466,7 +466,7 @@ int sdl_evaluation_params(sdl_eval_params_t which, const float* g, const void* c
 /* Where to put the flat model arrays (a memory-layout aid, not part of the method).  The calls take
  * any pointers, but their speed depends on how the arrays lie relative to each other: on MI355X the
  * fused step over 2 + 2M arrays that were allocated one by one (every base on its own 2 MiB-aligned
- * allocation) was measured 4-5 % slower than over the same arrays carved from ONE allocation, and
+ * allocation) was measured 2-6 % slower than over the same arrays carved from ONE allocation, and
  * another 1-2 % is gained when successive bases are staggered by 32 KiB on top of their 2 MiB-aligned
  * slots (the effect repeats with a period of 64 KiB).  sdl_flat_layout gives such a carving:
  * offsets[k], in bytes from a 2 MiB-aligned base, for k = g, mom, w_send[0..M), then, if
