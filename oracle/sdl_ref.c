@@ -31,7 +31,9 @@
  *     exponent 4) and in [256, 512) for E4M3 (largest exponent 8).  Variants of
  *     E3M0 use blocks of 64 or 128 elements, or the whole span (one scale per
  *     tensor, the 4.0 bits per parameter that the paper's table of exchanged
- *     data implies).
+ *     data implies).  One more variant (E3M0_RN) places a / scale in [8, 16)
+ *     instead, so that the block maximum is rounded to nearest rather than
+ *     saturated; which of the two the paper's own encoder does is unknown.
  *   - Rounding: nearest representable magnitude measured in the linear
  *     domain, ties to the even code, saturating at the largest magnitude.
  *   - Nibble order: element 2j in the low nibble of byte j, 2j+1 in the high.
@@ -44,7 +46,8 @@
  * E3M0 encoder is pinned only by mathematical properties (threshold table
  * derived by hand from the value set, closed form, exact round trips,
  * symmetry, scale invariance, error bound).  E3M0 versus the paper's own
- * encoder: parity unpinned.  E4M3, BF16, Nesterov and the merge are pinned
+ * encoder (either placement of the block maximum): parity unpinned.  E4M3,
+ * BF16, Nesterov and the merge are pinned
  * against library routines and closed forms in the CPU test-suite.
  */
 #include <math.h>
