@@ -1003,7 +1003,8 @@ size_t code_bytes_at(sdl_format_t fmt, uint64_t elem)
 // MI355X (medians of three runs over 302 M parameters, replica counts 2 / 4 / 8): the kernels
 // that write the replicas back want few wavefronts -- fused 12 / 8 / 8 (12 when w_send aliases
 // w_now), one-pass receive 12 / 8 / 8, merge 16 / 12 / 8 --, the receive side without the merge
-// 16 / 16 / all, and the send side every wavefront it can get.  A single replica: 16 for the fused
+// all / 16 / all (measured again with the arrays in one allocation: 16 cost it 3 % at two replicas),
+// and the send side every wavefront it can get.  A single replica: 16 for the fused
 // kernel and the one-pass receive, no cap otherwise.
 uint32_t lds_cap_bytes(int mode, uint32_t mt, bool aliased)
 {
@@ -1011,7 +1012,7 @@ uint32_t lds_cap_bytes(int mode, uint32_t mt, bool aliased)
     if (mode == kFused) return mt == 1 ? 10240u : ((aliased || mt == 2) ? 13653u : 20480u);
     if (mode == kReceive) return mt == 1 ? 10240u : (mt == 2 ? 13653u : 20480u);
     if (mode == kMerge) return mt == 1 ? 0u : (mt == 2 ? 10240u : (mt == 4 ? 13653u : 20480u));
-    if (mode == kReduce) return (mt == 2 || mt == 4) ? 10240u : 0u;
+    if (mode == kReduce) return mt == 4 ? 10240u : 0u;
     return 0u;
 }
 
