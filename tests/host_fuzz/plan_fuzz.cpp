@@ -48,7 +48,7 @@ int main() {
         // engine host logic
         uint32_t M = 1 + rng() % 4; std::vector<uint32_t> taus(M); for (auto& x : taus) x = rng() % (H + 1);
         sdl_engine_t* e = nullptr;
-        if (sdl_engine_create(plan, H, M, taus.data(), (sdl_format_t)(rng() % 7), 0.7f, 0.9f, 0.5f, &e) == SDL_OK) {
+        if (sdl_engine_create(plan, H, M, taus.data(), (sdl_format_t)(rng() % 8), 0.7f, 0.9f, 0.5f, &e) == SDL_OK) {
             if (sdl_engine_step(e, 1, nullptr, nullptr, nullptr) != SDL_ERR_INVALID_ARG) { printf("unbound engine stepped\n"); return 1; }
             static float fake[4];
             std::vector<void*> w(M, fake), msgs((size_t)nf * M, fake);

@@ -21,7 +21,7 @@ int sdl_plan_message_bytes(const sdl_plan_t* plan, uint32_t p, sdl_format_t fmt,
     const sdl_span_t* r; uint32_t n;
     int rc = sdl_plan_fragment_runs(plan, p, &r, &n);
     if (rc) return rc;
-    if ((int)fmt < 0 || (int)fmt > 6) return -1;
+    if ((int)fmt < 0 || (int)fmt > 7) return -1;
     if (c) *c = 0;
     if (s) *s = 0;
     return 0;
@@ -69,3 +69,36 @@ def test_plan_and_engine_host_logic_under_sanitizers(tmp_path):
     assert "engines walked" in res.stdout and "ERROR" not in res.stderr
     walked = int(res.stdout.split("engines walked")[1].split()[0])
     assert walked > 500
+
+
+@pytest.mark.skipif(shutil.which("g++") is None or shutil.which("nm") is None, reason="needs g++ and nm")
+def test_offloaded_engine_data_path_under_sanitizers(tmp_path):
+    """The schedule driver with the outer state in host memory, end to end on the CPU: csrc/sdl_offload.cpp against a
+    stand-in HIP runtime whose copies are memcpy, staged device calls that count, random plans / delays / pool sizes /
+    look-aheads (tests/host_fuzz/offload_fuzz.cpp).  A pool that is too small must be refused when it is bound, every
+    other walk must finish without running out of slots and leave the right counts in the host arrays."""
+    fake = os.path.join(ROOT, "tests", "host_fuzz", "fake_hip")
+    objs = []
+    for name, src, inc in (("plan", os.path.join(CSRC, "sdl_plan.cpp"), []), ("engine", os.path.join(CSRC, "sdl_engine.cpp"), []),
+                           ("offload", os.path.join(CSRC, "sdl_offload.cpp"), ["-I", fake]),
+                           ("fuzz", os.path.join(ROOT, "tests", "host_fuzz", "offload_fuzz.cpp"), [])):
+        obj = str(tmp_path / f"{name}.o")
+        _run(["g++", *FLAGS, *inc, "-c", src, "-o", obj])
+        objs.append(obj)
+    undefined = {l.split()[-1] for o in objs for l in _run(["nm", "-u", o]).stdout.splitlines() if " U sdl_" in l}
+    defined = {l.split()[-1] for o in objs for l in _run(["nm", "--defined-only", o]).stdout.splitlines()
+               if " T sdl_" in l}
+    rest = sorted(undefined - defined)
+    assert "sdl_receive_outer_step_staged" in defined and "sdl_offload_acquire" in defined
+    # what is left are the calls on flat device arrays, which an engine with offloaded state never makes
+    (tmp_path / "rest.c").write_text("#include <stdlib.h>\n" + "".join(f"int {n}() {{ abort(); }}\n" for n in rest))
+    _run(["gcc", "-g", "-c", str(tmp_path / "rest.c"), "-o", str(tmp_path / "rest.o")])
+    exe = str(tmp_path / "offload_fuzz")
+    _run(["g++", "-fsanitize=address,undefined", *objs, str(tmp_path / "rest.o"), "-o", exe])
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:verify_asan_link_order=0", UBSAN_OPTIONS="print_stacktrace=1")
+    res = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=900)
+    assert res.returncode == 0, res.stdout[-2000:] + res.stderr[-4000:]
+    assert "offload engines walked" in res.stdout and "ERROR" not in res.stderr
+    walked = int(res.stdout.split("offload engines walked")[1].split()[0])
+    refused = int(res.stdout.split("refused")[1].split()[0])
+    assert walked > 1000 and refused > 20
