@@ -235,7 +235,7 @@ def stream_check(plan, p: int, fmt: int, lr: float, mu: float, alpha: float, *, 
                                     _check_bytes(got_s, rs[m], f"{tag} scales[{m}] span@{off}+{a}")
                                     counts["scale_bytes"] += rs[m].size
             counts["elements"] += nb
-            if progress is not None:
+            if progress is not None and (bi + 1 == len(batches) or (bi + 1) % max(1, len(batches) // 6) == 0):
                 progress(f"{what}: batch {bi + 1}/{len(batches)}, {counts['elements']} elements compared, "
                          f"{time.time() - t_start:.0f} s")
     return counts
