@@ -14,7 +14,10 @@
  * the host; the *_plan forms of the calls work on whole fragments of a plan, and
  * sdl_engine_step drives them along the schedule.  sdl_offload_* keep the outer state
  * in host memory; sdl_outer_grad_cosine* and sdl_evaluation_params are the appendix's
- * diagnostics on the same arrays.  The M replicas ("workers") are M parameter arrays
+ * diagnostics on the same arrays.  sdl_fragment_outer_step_plan_static is the fused step
+ * for callers that cannot allocate; sdl_flat_layout says where to put the flat arrays and
+ * sdl_memory_probe measures what the memory system gives (neither is part of the method).
+ * The M replicas ("workers") are M parameter arrays
  * resident in one GPU's memory; no call communicates with another device.
  *
  * Conventions for every call
