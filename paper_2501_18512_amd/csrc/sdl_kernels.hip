@@ -1400,6 +1400,17 @@ static int launch_fragment(Args& a, const sdl_plan_t* plan, uint32_t p, Align16 
     if (rc != SDL_OK) return rc;
     const PieceWalk start{runs, pieces, n_runs, n_pieces, al, a.staged != 0u};
     PieceWalk::Piece pc;
+    const uint32_t tile = tile_elems(MODE, a, fmt);
+    {
+        // sizes are checked for every launch of the call before the first one is made
+        PieceWalk walk = start;
+        uint64_t n_wg = 0;
+        for (uint32_t in_group = 0; walk.next(&pc);) {
+            n_wg += (pc.numel + tile - 1) / tile;
+            if (n_wg > 0x7fffffffull) return SDL_ERR_UNSUPPORTED;
+            if (++in_group == (uint32_t)kMaxRuns) { in_group = 0; n_wg = 0; }
+        }
+    }
     if (is_span_scaled(fmt) && (MODE == kQuantize || MODE == kFused)) {
         // whole-span scale: clear the scale words, take the grid-wide maxima, then encode
         SpanRun batch[kAbsmaxMaxRuns];
@@ -1414,14 +1425,12 @@ static int launch_fragment(Args& a, const sdl_plan_t* plan, uint32_t p, Align16 
             }
         }
     }
-    const uint32_t tile = tile_elems(MODE, a, fmt);
     RunBuilder rb(&a, tile);
     PieceWalk walk = start;
     for (bool more = walk.next(&pc); more || a.n_runs;) {
         if (more) rb.add(pc.offset, pc.numel, pc.al.path(), pc.msg, pc.sidx, pc.soff);
         more = more && walk.next(&pc);
         if (rb.full() || !more) {
-            if (rb.n_wg > 0x7fffffffull) return SDL_ERR_UNSUPPORTED;
             if (launch<MODE>(a, fmt, (uint32_t)rb.n_wg, (hipStream_t)stream) != hipSuccess) return SDL_ERR_DEVICE;
             rb = RunBuilder(&a, tile);
         }
