@@ -431,7 +431,7 @@ int sdl_outer_grad_cosine_plan(const sdl_plan_t* plan, uint32_t p, const float* 
 
 /* Result of the union of n_sets disjoint parameter sets from their results (device memory,
  * results[k] at results + k * stride_doubles): the Gram matrices add, cos and mean follow.
- * This is how "all fragments but the embedding" is formed from per-fragment or per-span
+ * This is how the result for all fragments but the embedding is formed from per-fragment or per-span
  * results.  Needs no workspace. */
 int sdl_cosine_combine(const double* results, uint64_t stride_doubles, uint32_t n_sets, uint32_t M, double* result,
                        void* stream);

@@ -1,7 +1,7 @@
 // Host-side driver of Algorithm 2's outer-optimization schedule: at every inner step it
 // issues the send-side and receive-side calls of the fragments that are due (Section 2.2:
 // staggered fragments; Section 2.3: the result of a send is consumed tau steps later, with
-// an optional different delay per worker, Section 3.3.2 "slack between workers").
+// an optional different delay per worker, Section 3.3.2 on workers of unequal speed).
 // Uses only the plan-level entry points of sdl.h; no device code here.
 #include <algorithm>
 #include <new>
