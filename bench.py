@@ -295,6 +295,17 @@ def extras(st, fmt, wl, M, torch, sdl, args):
             frag_calls[name] = {"ms": t, "GB/s": nbytes / t / 1e6, "frac": nbytes / t / 1e6 / HBM_PEAK_GBS}
         res["fragment_calls"] = frag_calls
         del fc, fs
+        # the fused step in the whole-span (per-tensor) scale, the 4.0 bits per parameter of the paper's accounting:
+        # one more read pass over g and w_send for the grid-wide maxima (pre-pass + fused launch timed together)
+        span_fmt = sdl.FMT_E3M0_SPAN
+        words = [torch.zeros(max(sdl.sdl_plan_message_bytes(st.plan, st.fragment, span_fmt)[1], 4), dtype=torch.uint8,
+                             device="cuda") for _ in range(M)]
+        t = time_gpu(torch, lambda: sdl.sdl_fragment_outer_step_plan_ex(
+            st.plan, st.fragment, st.g, st.mom, st.w_send, st.w_now, span_fmt, wl.lr, wl.mu, wl.alpha, None, words),
+            steps, warm)
+        sbpp = algorithmic_bytes_per_param(M, wl.tau) + 4.0 + 2.0 * M
+        res["fused_whole_span_scale"] = {"ms": t, "GB/s": sbpp * st.n / t / 1e6, "frac": sbpp * st.n / t / 1e6 / HBM_PEAK_GBS,
+                                         "algorithmic_bytes_per_param": sbpp}
     # parameters handed to evaluation: fp32 mean of the replicas, written as bf16 (2M + 2 bytes per parameter)
     ev = torch.empty(n, dtype=torch.bfloat16, device="cuda")
     t = time_gpu(torch, lambda: sdl.sdl_evaluation_params(sdl.EVAL_REPLICA_MEAN, None, ws, n, ev), steps, warm)
