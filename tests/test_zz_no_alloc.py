@@ -91,3 +91,47 @@ def test_static_entry_point_rejects_more_spans_than_it_holds():
     sdl.sdl_fragment_outer_step_plan_static(plan, 0, g, mom, w_send, w_now, sdl.FMT_E3M0, 0.7, 0.9, 0.5)
     torch.cuda.synchronize()
     assert not torch.equal(before, g)
+
+
+@pytest.mark.gpu
+def test_static_entry_point_under_graph_capture():
+    """What the entry point is for: captured into a HIP graph (after one eager call, which looks the device
+    array's address up) and replayed several times with eager work in between; every replay must reproduce
+    the eager result of the same inputs bit for bit (the scale words are cleared by a fill kernel, not by a
+    memset node)."""
+    rng = np.random.default_rng(5)
+    plan = _plan([int(x) for x in rng.integers(1, 60000, 20)] + [131072, 77], 5, 2)
+    M, fmt, p = 3, sdl.FMT_E3M0_SPAN, 1
+    total = plan.total_numel
+    g0, mom0, w_send, wn0 = workloads.make_span(total, M, tau=1, delta="outliers", base_seed=9, device=DEV)
+    # eager reference through the workspace entry point
+    ge, me, we = g0.clone(), mom0.clone(), [w.clone() for w in wn0]
+    words = [torch.zeros(max(sdl.sdl_plan_message_bytes(plan, p, fmt)[1], 4), dtype=torch.uint8, device=DEV) for _ in range(M)]
+    sdl.sdl_fragment_outer_step_plan_ex(plan, p, ge, me, w_send, we, fmt, 0.7, 0.9, 0.5, None, words)
+    # the arrays the graph works on
+    g, mom, wn = g0.clone(), mom0.clone(), [w.clone() for w in wn0]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        sdl.sdl_fragment_outer_step_plan_static(plan, p, g, mom, w_send, wn, fmt, 0.7, 0.9, 0.5)   # eager, on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sdl.sdl_fragment_outer_step_plan_static(plan, p, g, mom, w_send, wn, fmt, 0.7, 0.9, 0.5)
+    for replay in range(4):
+        # restore the inputs with eager copies, dirty the device array with an eager call on another plan in between
+        g.copy_(g0), mom.copy_(mom0)
+        for a, b in zip(wn, wn0):
+            a.copy_(b)
+        if replay % 2:
+            small = _plan([5000, 77, 1024, 300], 2, 2)
+            sg, sm, sws, swn = workloads.make_span(small.total_numel, 2, tau=1, base_seed=replay, device=DEV)
+            sdl.sdl_fragment_outer_step_plan_static(small, 0, sg, sm, sws, swn, fmt, 0.7, 0.9, 0.5)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(g.view(torch.int32), ge.view(torch.int32)), f"replay {replay}: g"
+        assert torch.equal(mom.view(torch.int32), me.view(torch.int32)), f"replay {replay}: mom"
+        for a, b in zip(wn, we):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"replay {replay}: replica"
