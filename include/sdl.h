@@ -41,8 +41,11 @@
  *     are fetched twice); code arrays that are not 16-byte aligned put the whole
  *     call on an element-by-element path at a quarter of the speed.
  *   - 1 <= M <= SDL_MAX_WORKERS.
- *   - No two arrays may overlap, except that w_send[m] may be the very same
- *     pointer as w_now[m] for every m (no overlap delay, tau = 0).
+ *   - An array that a call writes must not overlap any other array of the call, except that
+ *     w_send[m] may be the very same pointer as w_now[m] for every m (no overlap delay,
+ *     tau = 0).  The span-level and fragment-level calls check this from the sizes they are
+ *     given (n, or the plan's model size) and return SDL_ERR_INVALID_ARG; arrays that are
+ *     only read may coincide.
  *   - Non-finite inputs: a block that contains Inf or NaN gets scale byte 0xff and
  *     decodes to NaN in every element (E3M0 / E4M3); BF16 / FP32 carry them through.
  */

@@ -1210,6 +1210,37 @@ struct RunBuilder {
     }
 };
 
+// The aliasing rule of the interface, checked: an array that a call writes must not overlap any other
+// array of the call (w_send[m] being the very same pointer as w_now[m] is the one exception, and then
+// only w_now[m] is listed).  model_elems / state_elems: elements of the replicas and of g / mom that the
+// call may touch; code_bytes / scale_bytes: size of one replica's message arrays.
+template <int MODE>
+bool arrays_clash(const Args& a, sdl_format_t fmt, uint64_t model_elems, uint64_t state_elems, size_t code_bytes,
+                  size_t scale_bytes)
+{
+    struct Range { uintptr_t lo, hi; bool written; };
+    Range r[2 + 4 * SDL_MAX_WORKERS];
+    int n = 0;
+    auto add = [&](const void* p, uint64_t bytes, bool written) {
+        if (p && bytes) { r[n].lo = reinterpret_cast<uintptr_t>(p); r[n].hi = r[n].lo + bytes; r[n].written = written; ++n; }
+    };
+    constexpr bool state_written = MODE == kReduce || MODE == kFused || MODE == kReceive;
+    add(a.g, state_elems * 4, state_written);
+    if constexpr (state_written) add(a.mom, state_elems * 4, true);
+    const bool msg_written = MODE == kQuantize || (MODE == kFused && a.emit);
+    const bool msg_used = msg_written || MODE == kReduce || MODE == kReceive;
+    for (uint32_t m = 0; m < a.M; ++m) {
+        if (MODE == kQuantize || (MODE == kFused && !a.aliased)) add(a.w_send[m], model_elems * 2, false);
+        if (MODE == kMerge || MODE == kFused || MODE == kReceive) add(a.w_now[m], model_elems * 2, true);
+        if (msg_used) add(a.codes[m], code_bytes, msg_written);
+        if (msg_used || (MODE == kFused && is_span_scaled(fmt))) add(a.scales[m], scale_bytes, msg_written || MODE == kFused);
+    }
+    for (int i = 0; i < n; ++i)
+        for (int j = i + 1; j < n; ++j)
+            if ((r[i].written || r[j].written) && r[i].lo < r[j].hi && r[j].lo < r[i].hi) return true;
+    return false;
+}
+
 // One span starting at the given pointers (offset 0).
 template <int MODE>
 int run_single_span(Args& a, uint64_t n, sdl_format_t fmt, Align16 al, void* stream)
@@ -1217,6 +1248,11 @@ int run_single_span(Args& a, uint64_t n, sdl_format_t fmt, Align16 al, void* str
     if (n == 0) return SDL_OK;
     const uint32_t tile = tile_elems(MODE, a, fmt);
     if (n > (uint64_t)0x7fffffff * (uint64_t)tile) return SDL_ERR_UNSUPPORTED;
+    {
+        size_t cb = 0, sb = 0;
+        sdl_exchange_bytes(fmt, n, &cb, &sb);
+        if (arrays_clash<MODE>(a, fmt, n, n, cb, sb)) return SDL_ERR_INVALID_ARG;
+    }
     RunBuilder rb(&a, tile);
     rb.add(0, n, al.path());
     if constexpr (MODE == kQuantize || MODE == kFused) {
@@ -1475,6 +1511,17 @@ static int launch_fragment(Args& a, const sdl_plan_t* plan, uint32_t p, Align16 
             if (n_wg > 0x7fffffffull) return SDL_ERR_UNSUPPORTED;
             if (++in_group == (uint32_t)kMaxRuns) { in_group = 0; n_wg = 0; }
         }
+    }
+    {
+        // the replicas are flat model arrays; g / mom too, unless they are a staging buffer of this fragment
+        size_t cb = 0, sb = 0;
+        if (MODE != kMerge) {
+            rc = sdl_plan_message_bytes(plan, p, fmt, &cb, &sb);
+            if (rc != SDL_OK) return rc;
+        }
+        const uint64_t model = sdl_plan_total_numel(plan);
+        if (arrays_clash<MODE>(a, fmt, model, a.staged ? sdl_plan_staged_numel(plan, p) : model, cb, sb))
+            return SDL_ERR_INVALID_ARG;
     }
     if (is_span_scaled(fmt) && (MODE == kQuantize || MODE == kFused)) {
         // whole-span scale: clear the scale words, take the grid-wide maxima, then encode

@@ -161,6 +161,24 @@ def test_device_calls_reject_bad_arguments_before_launch():
     with pytest.raises(sdl.SdlError) as e:
         sdl.sdl_dequant_reduce_nesterov(good, 0, [good], [good], 64, sdl.FMT_E3M0, 0.7, 0.9, stream=0)
     assert e.value.status == -1
+    # an array that is written overlaps another array of the call (all pointers valid and aligned otherwise)
+    A = 0x100000                                                                           # arrays 1 MiB apart
+    for call in (
+            lambda: sdl.sdl_fragment_outer_step(A, A + 128, [2 * A, 3 * A], [4 * A, 5 * A], 64, sdl.FMT_E3M0,
+                                                0.7, 0.9, 0.5, stream=0),                  # mom inside g
+            lambda: sdl.sdl_fragment_outer_step(A, 2 * A, [3 * A, 4 * A], [5 * A, 5 * A + 64], 64, sdl.FMT_E3M0,
+                                                0.7, 0.9, 0.5, stream=0),                  # two replicas overlap
+            lambda: sdl.sdl_fragment_outer_step(A, 2 * A, [3 * A, 4 * A], [5 * A, 3 * A], 64, sdl.FMT_E3M0,
+                                                0.7, 0.9, 0.5, stream=0),                  # w_now[1] is w_send[0]
+            lambda: sdl.sdl_quantize_outer_grad(A, [2 * A], 64, sdl.FMT_E3M0, [2 * A + 64], [3 * A], stream=0),
+            lambda: sdl.sdl_quantize_outer_grad(A, [2 * A], 64, sdl.FMT_E3M0, [3 * A], [3 * A + 16], stream=0),
+            lambda: sdl.sdl_dequant_reduce_nesterov(A, A, [2 * A], [3 * A], 64, sdl.FMT_E3M0, 0.7, 0.9, stream=0),
+            lambda: sdl.sdl_dequant_reduce_nesterov(A, 2 * A, [A + 16], [3 * A], 64, sdl.FMT_E3M0, 0.7, 0.9, stream=0),
+            lambda: sdl.sdl_merge_overlap(A, [2 * A, 2 * A], 64, 0.5, stream=0),
+            lambda: sdl.sdl_merge_overlap(A, [A + 200], 64, 0.5, stream=0)):
+        with pytest.raises(sdl.SdlError) as e:
+            call()
+        assert e.value.status == -1
     # n == 0 is a no-op that touches nothing
     sdl.sdl_quantize_outer_grad(0, [0], 0, sdl.FMT_E3M0, [0], [0], stream=0)
     sdl.sdl_fragment_outer_step(0, 0, [0], [0], 0, sdl.FMT_E3M0, 0.7, 0.9, 0.5, stream=0)
